@@ -1,0 +1,171 @@
+/*
+ * ss.h -- C ABI of the 2:4 semi-structured-sparse convolution library for AMD MI355X (gfx950).
+ *
+ * The library computes the inference-time masked convolution of
+ * "Inducing Semi-Structured Sparsity by Masking for Efficient Model Inference in Convolutional
+ * Networks" (Sec. 3.3, Eq. 6):
+ *
+ *        Y = (M (.) W) * U(X)
+ *
+ * where W in R^{cout x K}, K = cin*kh*kw, is the weight matrix built from the cout kernels
+ * (Eq. 5), M in {0,1}^{cout x K} is a 2:4 mask (Sec. 3.1, Eq. 2: every block of 4 consecutive
+ * entries of a row holds exactly two ones), and U is the unfold operator, which is never
+ * materialised.  W and M are inputs and are never written: the original weights stay unchanged
+ * (abstract; Sec. 3.1, last paragraph).
+ *
+ * General conventions
+ *   - Every function returns an int status: SS_OK (0) or a negative SS_ERR_* code.  Nothing throws.
+ *   - Unless a parameter is marked [host], every data pointer is a DEVICE pointer.  The caller
+ *     owns every buffer; the library never allocates or frees device memory and keeps no state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The convolution
+ *     calls only enqueue work on it and return; ss_mask_compress additionally waits for the
+ *     stream once, because it reports the mask's validity.
+ *   - 16-bit element types: SS_F16 (IEEE binary16) and SS_BF16 (bfloat16).  Activations, weights
+ *     and outputs of one call share the type.  Products are accumulated in fp32, the bias is
+ *     fp32, and the result is rounded once (round-to-nearest-even) when it is stored.
+ *   - Activations and outputs are NHWC: x[N][H][Wd][cin], y[N][Ho][Wo][cout], with
+ *     Ho = floor((H + 2*pad_h - kh)/stride_h) + 1 and likewise Wo.  Zero padding, no dilation,
+ *     no groups (grouped convolutions are left dense by the method, Sec. 4 "Architectures").
+ *   - The operation is a cross-correlation, as Eq. (4) writes it: input row = ho*stride_h - pad_h + r.
+ *   - Flattening of (c, r, t) into the reduction index k, which decides which 4 weights form a
+ *     block:  SS_K_CRS  k = (c*kh + r)*kw + t   (channel slowest; the order in which Eq. (5)
+ *                                                builds W from the kernels; default)
+ *             SS_K_RSC  k = (r*kw + t)*cin + c   (channels-last flattening)
+ *     For 1x1 kernels the two coincide.
+ *   - K must be a multiple of 4 per row (blocks never straddle rows); otherwise the layer is
+ *     rejected with SS_ERR_UNSUPPORTED and stays dense at the caller's side (Sec. 3.3, last
+ *     paragraph, leaves the augmentation to the user).
+ */
+#ifndef SS_H_
+#define SS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SS_OK = 0,
+    SS_ERR_INVALID_ARG = -1, /* null required pointer, non-positive size, unknown enum, empty output */
+    SS_ERR_BAD_MASK    = -2, /* a block of 4 mask entries without exactly two ones (or an entry > 1) */
+    SS_ERR_UNSUPPORTED = -3, /* K % 4 != 0, or sizes beyond 32-bit index limits */
+    SS_ERR_WORKSPACE   = -4, /* workspace smaller than ss_conv2d_workspace_bytes reports */
+    SS_ERR_HIP         = -5  /* a HIP runtime call failed (launch error, no device, ...) */
+};
+
+enum { SS_F16 = 0, SS_BF16 = 1 };
+enum { SS_K_CRS = 0, SS_K_RSC = 1 };
+enum { SS_ACT_NONE = 0, SS_ACT_RELU = 1 };
+
+/* Describes one weight matrix W in R^{cout x (cin*kh*kw)} (Eq. 5).  Plain data, passed by pointer [host]. */
+typedef struct {
+    int32_t cout, cin, kh, kw;
+    int32_t dtype;  /* SS_F16 | SS_BF16 */
+    int32_t korder; /* SS_K_CRS | SS_K_RSC */
+} ss_weight_desc;
+
+/* Human-readable name of a status code.  Never NULL.  [host] */
+const char *ss_status_string(int status);
+
+/*
+ * Size in bytes of the packed (structured) representation that ss_mask_compress writes and
+ * ss_conv2d_fwd reads (Fig. 1: surviving values + a 2-bit position index each).
+ *
+ * Device layout, with Mt = ceil(cout/32) row tiles and Ks = ceil(K/32) reduction steps:
+ *   bytes [0, 256)       header, 64 little-endian uint32:
+ *                        [0]=0x34325353 [1]=1 [2]=cout [3]=cin [4]=kh [5]=kw [6]=dtype [7]=korder
+ *                        [8]=Mt [9]=Ks [10]=index of the first invalid block (row*K/4+block) or
+ *                        0xFFFFFFFF if the mask is valid, rest 0
+ *   values               Mt*Ks tiles of 64 lanes x 8 elements (16 bytes per lane, 1 KiB per tile),
+ *                        tile (mt, ks) at 256 + (mt*Ks + ks)*1024.  Lane l, slot s holds, for row
+ *                        o = 32*mt + l%32 and block g = 8*ks + 4*(s/4) + 2*(l/32) + (s/2)%2 of that
+ *                        row, the (s%2)-th kept weight of the block (ascending position).
+ *   metadata             Mt*ceil(Ks/2) tiles of 64 uint32, after the values.  Lane l of tile
+ *                        (mt, ks/2) holds in its low (ks even) or high (ks odd) 16 bits four
+ *                        nibbles, nibble j (bits 4j..4j+3) = i0 | (i1 << 2) for the block held in
+ *                        slots 2j, 2j+1 of the same lane of value tile (mt, ks); i0 < i1 are the
+ *                        kept positions inside the block.
+ *   Rows >= cout and blocks >= K/4 are padding: values +0, nibble 0x4.
+ * This is the operand layout of gfx950's V_SMFMAC_F32_32X32X32_{F16,BF16} (sparse A operand and
+ * its index register), so the convolution loads it straight into registers.
+ */
+int ss_packed_bytes(const ss_weight_desc *desc, size_t *packed_bytes /*[host] out*/);
+
+/*
+ * Size in bytes of the dense tiled copy of M (.) W that ss_dense_pack writes and
+ * ss_conv2d_dense_fwd reads: a 256-byte header as above (magic 0x44325353) followed by
+ * Mt*Ks*2 tiles of 64 lanes x 8 elements; tile (mt, ks, h) lane l slot s holds
+ * (M (.) W)[32*mt + l%32][32*ks + 16*(l/32) + 8*h + s], zero where out of range.
+ */
+int ss_dense_bytes(const ss_weight_desc *desc, size_t *dense_bytes /*[host] out*/);
+
+/*
+ * Weight compressor (Fig. 1; Sec. 3.1 Eq. 2 for the validity rule).
+ *   W       [cout][K] 16-bit elements, flattening per desc->korder          (read only)
+ *   M       [cout][K] bytes, each 0 or 1                                    (read only)
+ *   packed  ss_packed_bytes(desc) bytes, 256-byte aligned                   (written)
+ *   bad_row_group [host, optional] two int32: on SS_ERR_BAD_MASK receives the row and the block
+ *           index of the first (row-major) invalid block.
+ * Values are copied bit for bit: a kept weight that is -0, NaN or subnormal is preserved.
+ * Waits for `stream`.  On SS_ERR_BAD_MASK the contents of `packed` must not be used.
+ */
+int ss_mask_compress(const ss_weight_desc *desc, const void *W, const uint8_t *M,
+                     void *packed, int32_t *bad_row_group, void *stream);
+
+/*
+ * Inverse of the compressor: writes M (.) W as a plain [cout][K] matrix (desc->korder), +0 at
+ * the dropped positions.  Test and debugging aid; asynchronous on `stream`.
+ */
+int ss_mask_decompress(const ss_weight_desc *desc, const void *packed, void *W_masked_out,
+                       void *stream);
+
+/*
+ * Builds the dense twin's operand: the entry-wise product M (.) W (Eq. 6) in the tiled layout
+ * described at ss_dense_bytes.  M == NULL means an all-ones mask (plain dense layer).  The mask
+ * is not validated here.  Asynchronous on `stream`.
+ */
+int ss_dense_pack(const ss_weight_desc *desc, const void *W, const uint8_t *M, void *dense,
+                  void *stream);
+
+/*
+ * Scratch the convolution needs for the given problem (fp32 partial sums when the reduction is
+ * split across workgroups; 0 when it is not).  Same value for the sparse and the dense call.
+ */
+int ss_conv2d_workspace_bytes(const ss_weight_desc *desc, int32_t N, int32_t H, int32_t Wd,
+                              int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                              size_t *bytes /*[host] out*/);
+
+/*
+ * Masked convolution, Eq. (6), with the layer model sigma(Wx + b) of Lemma 3.1 fused:
+ *     y[n,ho,wo,o] = act( bias[o] + sum_{c,r,t} (M (.) W)[o,k(c,r,t)] * x[n, ho*sh-ph+r, wo*sw-pw+t, c] )
+ * Only the two kept products of each block are issued (gfx950 sparse MFMA).
+ *   x         [N][H][Wd][cin]    16-bit, desc->dtype                        (read only)
+ *   packed    buffer written by ss_mask_compress for the same desc          (read only)
+ *   bias      [cout] fp32, or NULL for no bias                              (read only)
+ *   act       SS_ACT_NONE | SS_ACT_RELU
+ *   y         [N][Ho][Wo][cout]  16-bit, desc->dtype                        (written)
+ *   workspace ws_bytes >= ss_conv2d_workspace_bytes(...) bytes, 256-byte aligned; may be NULL
+ *             when that size is 0.  Contents are scratch.
+ * Asynchronous on `stream`; launch errors are returned as SS_ERR_HIP.
+ */
+int ss_conv2d_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                  const void *packed, const float *bias,
+                  int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
+                  void *y, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * The same-design dense twin: identical tiling, staging and epilogue, with the dense MFMA
+ * instruction on the operand built by ss_dense_pack.  Denominator of the speed-up metric, and
+ * the path for layers that stay dense.
+ */
+int ss_conv2d_dense_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                        const void *dense, const float *bias,
+                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
+                        void *y, void *workspace, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SS_H_ */

@@ -1,0 +1,177 @@
+"""CPU oracle for the 2:4 masked convolution -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over ``ss_oracle.c`` (plain C, fp64) plus the index-arithmetic description
+of the device tile layout in ``device_layout.py``.  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg import this package; the GPU product path never does, and this
+package imports nothing from the GPU package.
+
+Paper passages followed: Sec. 3.1 Eq. (2) (mask validity), Fig. 1 (structured representation),
+Sec. 3.3 Eq. (4) (direct convolution) and Eq. (6) (masked convolution).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "ss_oracle.c"
+_LIB = _HERE / "libss_oracle.so"
+
+F16, BF16 = 0, 1
+K_CRS, K_RSC = 0, 1
+ACT_NONE, ACT_RELU = 0, 1
+
+
+def build(force: bool = False) -> Path:
+    """Compile the C oracle with gcc (-O2, OpenMP).  Rebuilds when the source is newer."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", str(tmp), str(_SRC), "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        i64, p = ctypes.c_int64, ctypes.c_void_p
+        lib.ss_oracle_bits_to_double.restype = ctypes.c_double
+        lib.ss_oracle_bits_to_double.argtypes = [ctypes.c_uint16, ctypes.c_int]
+        lib.ss_oracle_num_threads.restype = ctypes.c_int
+        lib.ss_oracle_mask_check.restype = ctypes.c_int
+        lib.ss_oracle_mask_check.argtypes = [p, i64, i64, p, p]
+        lib.ss_oracle_compress.restype = ctypes.c_int
+        lib.ss_oracle_compress.argtypes = [p, p, i64, i64, p, p]
+        lib.ss_oracle_decompress.restype = None
+        lib.ss_oracle_decompress.argtypes = [p, p, i64, i64, p]
+        lib.ss_oracle_conv2d.restype = ctypes.c_int
+        lib.ss_oracle_conv2d.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
+                                         ctypes.c_int, ctypes.c_int, p, i64, i64, i64, i64,
+                                         ctypes.c_int, p]
+        lib.ss_oracle_conv2d_points.restype = ctypes.c_int
+        lib.ss_oracle_conv2d_points.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
+                                                ctypes.c_int, ctypes.c_int, p, i64, i64, i64, i64,
+                                                ctypes.c_int, p, i64, p]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().ss_oracle_num_threads())
+
+
+def bits_to_double(bits, dtype: int) -> np.ndarray:
+    """Exact value of fp16 / bf16 bit patterns (uint16 array) as float64, via the C routine."""
+    lib = _load()
+    b = np.asarray(bits, dtype=np.uint16)
+    out = np.empty(b.shape, dtype=np.float64)
+    fb, fo = b.reshape(-1), out.reshape(-1)
+    for i in range(fb.size):
+        fo[i] = lib.ss_oracle_bits_to_double(int(fb[i]), dtype)
+    return out
+
+
+def mask_check(M) -> tuple[int, int, int]:
+    """(status, row, group): status 0 = valid 2:4 mask, 1 = invalid block, 2 = K % 4 != 0."""
+    M = _c(M, np.uint8)
+    cout, K = M.shape
+    r, g = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    st = _load().ss_oracle_mask_check(_ptr(M), cout, K, ctypes.byref(r), ctypes.byref(g))
+    return int(st), int(r.value), int(g.value)
+
+
+def compress(W_bits, M):
+    """Canonical structured form: (vals uint16 [cout, K/2], meta uint8 [cout, K/4])."""
+    W_bits, M = _c(W_bits, np.uint16), _c(M, np.uint8)
+    cout, K = W_bits.shape
+    assert M.shape == (cout, K)
+    if K % 4:
+        raise ValueError("K % 4 != 0")
+    vals = np.zeros((cout, K // 2), dtype=np.uint16)
+    meta = np.zeros((cout, K // 4), dtype=np.uint8)
+    st = _load().ss_oracle_compress(_ptr(W_bits), _ptr(M), cout, K, _ptr(vals), _ptr(meta))
+    if st:
+        raise ValueError(f"invalid 2:4 mask (status {st})")
+    return vals, meta
+
+
+def decompress(vals, meta) -> np.ndarray:
+    vals, meta = _c(vals, np.uint16), _c(meta, np.uint8)
+    cout, G = meta.shape
+    K = 4 * G
+    out = np.empty((cout, K), dtype=np.uint16)
+    _load().ss_oracle_decompress(_ptr(vals), _ptr(meta), cout, K, _ptr(out))
+    return out
+
+
+def _out_hw(H, Wd, kh, kw, stride, pad):
+    return (H + 2 * pad[0] - kh) // stride[0] + 1, (Wd + 2 * pad[1] - kw) // stride[1] + 1
+
+
+def conv2d(x_bits, W_bits, M, *, cin, kh, kw, korder=K_CRS, dtype=F16, bias=None,
+           stride=(1, 1), pad=(0, 0), act=ACT_NONE) -> np.ndarray:
+    """Masked convolution, fp64, NHWC in / NHWC out, not rounded.  M=None: plain dense conv."""
+    x_bits, W_bits = _c(x_bits, np.uint16), _c(W_bits, np.uint16)
+    N, H, Wd, c = x_bits.shape
+    assert c == cin
+    cout, K = W_bits.shape
+    assert K == cin * kh * kw
+    if M is not None:
+        M = _c(M, np.uint8)
+        assert M.shape == (cout, K)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+        assert bias.shape == (cout,)
+    Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    y = np.empty((N, Ho, Wo, cout), dtype=np.float64)
+    st = _load().ss_oracle_conv2d(_ptr(x_bits), N, H, Wd, cin, _ptr(W_bits), _ptr(M), cout, kh, kw,
+                                  korder, dtype, _ptr(bias), stride[0], stride[1], pad[0], pad[1],
+                                  act, _ptr(y))
+    if st:
+        raise ValueError(f"oracle conv2d failed (status {st})")
+    return y
+
+
+def conv2d_points(x_bits, W_bits, M, flat_idx, *, cin, kh, kw, korder=K_CRS, dtype=F16, bias=None,
+                  stride=(1, 1), pad=(0, 0), act=ACT_NONE) -> np.ndarray:
+    """The same definition at sampled flat NHWC output indices only."""
+    x_bits, W_bits = _c(x_bits, np.uint16), _c(W_bits, np.uint16)
+    N, H, Wd, c = x_bits.shape
+    assert c == cin
+    cout, K = W_bits.shape
+    if M is not None:
+        M = _c(M, np.uint8)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    flat_idx = _c(flat_idx, np.int64)
+    Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
+    assert flat_idx.min() >= 0 and flat_idx.max() < N * Ho * Wo * cout
+    out = np.empty(flat_idx.shape, dtype=np.float64)
+    st = _load().ss_oracle_conv2d_points(_ptr(x_bits), N, H, Wd, cin, _ptr(W_bits), _ptr(M), cout,
+                                         kh, kw, korder, dtype, _ptr(bias), stride[0], stride[1],
+                                         pad[0], pad[1], act, _ptr(flat_idx), flat_idx.size, _ptr(out))
+    if st:
+        raise ValueError(f"oracle conv2d_points failed (status {st})")
+    return out

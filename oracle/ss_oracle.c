@@ -1,0 +1,242 @@
+/*
+ * CPU oracle for the 2:4 semi-structured-sparse convolution.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the GPU library is
+ * checked against.  Only the tests, the smoke check and the benchmark's CPU-baseline leg may
+ * call it; the product path never does.  It shares no code, header, table or helper with the
+ * HIP sources.
+ *
+ * What it follows (paper: "Inducing Semi-Structured Sparsity by Masking for Efficient Model
+ * Inference in Convolutional Networks"):
+ *   - Sec. 3.1, Eq. (2): the mask M is row-major, tiled left to right by blocks of 4 contiguous
+ *     entries, each block holding exactly two ones (N:M sparsity with N=2, M=4; six patterns).
+ *   - Fig. 1: the structured representation keeps only the surviving values plus a 2-bit
+ *     position index for each of them.
+ *   - Sec. 3.3, Eq. (4): direct 2-D convolution with zero padding (a cross-correlation: the
+ *     input index is the sum of the output index and the kernel offset).
+ *   - Sec. 3.3, Eq. (6): the masked convolution is the convolution with M (.) W in place of W.
+ *
+ * Arithmetic: inputs are the exact values of their fp16 / bf16 bit patterns; every product and
+ * the running sum are fp64; the bias is fp32 widened to fp64; the result is NOT rounded.
+ *
+ * Weight matrices are [cout][K] with K = cin*kh*kw and one of two flattenings of (c, r, t):
+ *   korder 0 ("CRS", the paper's: channel slowest, kernel column fastest)  k = (c*kh + r)*kw + t
+ *   korder 1 ("RSC", channels-last flattening)                             k = (r*kw + t)*cin + c
+ * Activations are NHWC, outputs are NHWC.
+ *
+ * Parity pins (tests, CPU only): unfold+matmul (Eq. 5) in numpy, a float64 library conv,
+ * one-hot-kernel shifts, all-ones closed forms, linearity, 1x1 == matmul, brute-force over the
+ * six patterns, round trip, byte count 9/16.  No function here is "parity unpinned".
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <stdlib.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* dtype: 0 = IEEE binary16, 1 = bfloat16.  Exact widening of a 16-bit pattern to double. */
+double ss_oracle_bits_to_double(uint16_t bits, int dtype)
+{
+    if (dtype == 1) {
+        uint32_t u = ((uint32_t)bits) << 16;
+        float f;
+        memcpy(&f, &u, sizeof f);
+        return (double)f;
+    }
+    int sign = (bits >> 15) & 1;
+    int expo = (bits >> 10) & 0x1f;
+    int frac = bits & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -24);            /* subnormal: frac * 2^-10 * 2^-14 */
+    } else if (expo == 31) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(frac + 1024), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+    }
+    return sign ? -v : v;
+}
+
+int ss_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Sec. 3.1 / Eq. (2): every block of 4 consecutive entries of a row of M holds exactly two
+ * ones and every entry is 0 or 1.  Returns 0 if valid, else 1 and the first offending
+ * (row, group) in row-major order. */
+int ss_oracle_mask_check(const uint8_t *M, int64_t cout, int64_t K, int64_t *bad_row, int64_t *bad_group)
+{
+    if (K % 4 != 0) {
+        if (bad_row) *bad_row = -1;
+        if (bad_group) *bad_group = -1;
+        return 2;
+    }
+    for (int64_t o = 0; o < cout; o++) {
+        for (int64_t g = 0; g < K / 4; g++) {
+            int ones = 0, ok = 1;
+            for (int e = 0; e < 4; e++) {
+                uint8_t m = M[o * K + 4 * g + e];
+                if (m > 1) ok = 0;
+                ones += (m == 1);
+            }
+            if (!ok || ones != 2) {
+                if (bad_row) *bad_row = o;
+                if (bad_group) *bad_group = g;
+                return 1;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Fig. 1: canonical structured representation.
+ *   vals[o][2g], vals[o][2g+1] = the bit patterns of the two kept weights of group g, in
+ *                                ascending position order (copied, never converted);
+ *   meta[o][g]                 = i0 | (i1 << 2), one byte per group (values 0..15), where
+ *                                i0 < i1 are the kept positions inside the group.
+ * Returns 0, or the mask-check status if the mask is invalid (outputs then undefined). */
+int ss_oracle_compress(const uint16_t *W, const uint8_t *M, int64_t cout, int64_t K,
+                       uint16_t *vals, uint8_t *meta)
+{
+    int st = ss_oracle_mask_check(M, cout, K, NULL, NULL);
+    if (st) return st;
+    int64_t G = K / 4;
+    for (int64_t o = 0; o < cout; o++) {
+        for (int64_t g = 0; g < G; g++) {
+            int pos[2], n = 0;
+            for (int e = 0; e < 4; e++)
+                if (M[o * K + 4 * g + e]) pos[n++] = e;
+            vals[o * (K / 2) + 2 * g + 0] = W[o * K + 4 * g + pos[0]];
+            vals[o * (K / 2) + 2 * g + 1] = W[o * K + 4 * g + pos[1]];
+            meta[o * G + g] = (uint8_t)(pos[0] | (pos[1] << 2));
+        }
+    }
+    return 0;
+}
+
+/* Inverse of the above: rebuilds M (.) W, writing +0 at the two dropped positions. */
+void ss_oracle_decompress(const uint16_t *vals, const uint8_t *meta, int64_t cout, int64_t K,
+                          uint16_t *Wm)
+{
+    int64_t G = K / 4;
+    for (int64_t o = 0; o < cout; o++) {
+        for (int64_t g = 0; g < G; g++) {
+            for (int e = 0; e < 4; e++) Wm[o * K + 4 * g + e] = 0;
+            int i0 = meta[o * G + g] & 3, i1 = (meta[o * G + g] >> 2) & 3;
+            Wm[o * K + 4 * g + i0] = vals[o * (K / 2) + 2 * g + 0];
+            Wm[o * K + 4 * g + i1] = vals[o * (K / 2) + 2 * g + 1];
+        }
+    }
+}
+
+static int64_t kflat(int korder, int64_t c, int64_t r, int64_t t, int64_t cin, int64_t kh, int64_t kw)
+{
+    return korder == 0 ? (c * kh + r) * kw + t : (r * kw + t) * cin + c;
+}
+
+/* Eq. (4) with H <- M (.) W (Eq. 6), for cout kernels, a batch of N inputs, strides and
+ * symmetric zero padding; bias and activation follow the layer model sigma(Wx + b) of
+ * Lemma 3.1 with sigma in {identity (act=0), ReLU (act=1)}.
+ *   x    [N][H][Wd][cin]     16-bit patterns (dtype)
+ *   W    [cout][K]           16-bit patterns, flattening per korder
+ *   M    [cout][K]           0/1 bytes; NULL means all ones (plain dense convolution)
+ *   bias [cout] fp32 or NULL
+ *   y    [N][Ho][Wo][cout]   fp64, not rounded
+ * Returns 0, or 3 if the output would be empty. */
+int ss_oracle_conv2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin,
+                     const uint16_t *W, const uint8_t *M, int64_t cout, int64_t kh, int64_t kw,
+                     int korder, int dtype, const float *bias,
+                     int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, int act,
+                     double *y)
+{
+    int64_t Ho = (H + 2 * pad_h - kh) / stride_h + 1;
+    int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
+    if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
+    int64_t K = cin * kh * kw;
+
+    /* exact widening of the operands, and the entry-wise product M (.) W */
+    double *xd = (double *)malloc(sizeof(double) * (size_t)(N * H * Wd * cin));
+    double *wd = (double *)malloc(sizeof(double) * (size_t)(cout * K));
+    if (!xd || !wd) { free(xd); free(wd); return 4; }
+    for (int64_t i = 0; i < N * H * Wd * cin; i++) xd[i] = ss_oracle_bits_to_double(x[i], dtype);
+    for (int64_t i = 0; i < cout * K; i++)
+        wd[i] = (M == NULL || M[i]) ? ss_oracle_bits_to_double(W[i], dtype) : 0.0;
+
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; n++) {
+        for (int64_t ho = 0; ho < Ho; ho++) {
+            for (int64_t wo = 0; wo < Wo; wo++) {
+                for (int64_t o = 0; o < cout; o++) {
+                    double acc = 0.0;
+                    for (int64_t c = 0; c < cin; c++) {
+                        for (int64_t r = 0; r < kh; r++) {
+                            int64_t ih = ho * stride_h - pad_h + r;
+                            if (ih < 0 || ih >= H) continue;          /* zero padding */
+                            for (int64_t t = 0; t < kw; t++) {
+                                int64_t iw = wo * stride_w - pad_w + t;
+                                if (iw < 0 || iw >= Wd) continue;     /* zero padding */
+                                acc += wd[o * K + kflat(korder, c, r, t, cin, kh, kw)] *
+                                       xd[((n * H + ih) * Wd + iw) * cin + c];
+                            }
+                        }
+                    }
+                    if (bias) acc += (double)bias[o];
+                    if (act == 1 && !(acc > 0.0)) acc = (acc != acc) ? acc : 0.0;
+                    y[((n * Ho + ho) * Wo + wo) * cout + o] = acc;
+                }
+            }
+        }
+    }
+    free(xd);
+    free(wd);
+    return 0;
+}
+
+/* Same definition, evaluated only at `npts` sampled outputs (flat NHWC indices into y);
+ * out[i] receives y[flat_idx[i]].  Used for parity at sizes where the full tensor would
+ * take the CPU too long. */
+int ss_oracle_conv2d_points(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin,
+                            const uint16_t *W, const uint8_t *M, int64_t cout, int64_t kh, int64_t kw,
+                            int korder, int dtype, const float *bias,
+                            int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, int act,
+                            const int64_t *flat_idx, int64_t npts, double *out)
+{
+    int64_t Ho = (H + 2 * pad_h - kh) / stride_h + 1;
+    int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
+    if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
+    int64_t K = cin * kh * kw;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < npts; i++) {
+        int64_t f = flat_idx[i];
+        int64_t o = f % cout; f /= cout;
+        int64_t wo = f % Wo; f /= Wo;
+        int64_t ho = f % Ho; f /= Ho;
+        int64_t n = f;
+        double acc = 0.0;
+        for (int64_t c = 0; c < cin; c++)
+            for (int64_t r = 0; r < kh; r++) {
+                int64_t ih = ho * stride_h - pad_h + r;
+                if (ih < 0 || ih >= H) continue;
+                for (int64_t t = 0; t < kw; t++) {
+                    int64_t iw = wo * stride_w - pad_w + t;
+                    if (iw < 0 || iw >= Wd) continue;
+                    int64_t k = kflat(korder, c, r, t, cin, kh, kw);
+                    if (M != NULL && !M[o * K + k]) continue;
+                    acc += ss_oracle_bits_to_double(W[o * K + k], dtype) *
+                           ss_oracle_bits_to_double(x[((n * H + ih) * Wd + iw) * cin + c], dtype);
+                }
+            }
+        if (bias) acc += (double)bias[o];
+        if (act == 1 && !(acc > 0.0)) acc = (acc != acc) ? acc : 0.0;
+        out[i] = acc;
+    }
+    return 0;
+}
