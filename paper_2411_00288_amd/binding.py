@@ -1,0 +1,214 @@
+"""ctypes binding over the C ABI declared in include/ss.h.
+
+Argument marshalling only: every step of the path (compression, convolution, epilogue) runs in
+the HIP library.  PyTorch provides device memory and the stream.  There is no fallback: if the
+library has not been built, importing fails with an instruction to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libss.so"
+
+SS_OK = 0
+SS_ERR_INVALID_ARG, SS_ERR_BAD_MASK, SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP = -1, -2, -3, -4, -5
+SS_F16, SS_BF16 = 0, 1
+SS_K_CRS, SS_K_RSC = 0, 1
+SS_ACT_NONE, SS_ACT_RELU = 0, 1
+
+EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
+           "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd"]
+
+
+class ss_weight_desc(ctypes.Structure):
+    _fields_ = [("cout", ctypes.c_int32), ("cin", ctypes.c_int32), ("kh", ctypes.c_int32), ("kw", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("korder", ctypes.c_int32)]
+
+
+class SSError(RuntimeError):
+    def __init__(self, status: int, what: str, detail=None):
+        self.status = status
+        self.detail = detail
+        super().__init__(f"{what}: {status_string(status)}" + (f" {detail}" if detail is not None else ""))
+
+
+def _load() -> ctypes.CDLL:
+    if not LIB_PATH.exists():
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+            "or python paper_2411_00288_amd/build.py). There is no CPU fallback.")
+    lib = ctypes.CDLL(str(LIB_PATH))
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    dp = ctypes.POINTER(ss_weight_desc)
+    lib.ss_status_string.restype = ctypes.c_char_p
+    lib.ss_status_string.argtypes = [ctypes.c_int]
+    lib.ss_packed_bytes.argtypes = [dp, ctypes.POINTER(sz)]
+    lib.ss_dense_bytes.argtypes = [dp, ctypes.POINTER(sz)]
+    lib.ss_mask_compress.argtypes = [dp, vp, vp, vp, ctypes.POINTER(i32), vp]
+    lib.ss_mask_decompress.argtypes = [dp, vp, vp, vp]
+    lib.ss_dense_pack.argtypes = [dp, vp, vp, vp, vp]
+    lib.ss_conv2d_workspace_bytes.argtypes = [dp, i32, i32, i32, i32, i32, i32, i32, ctypes.POINTER(sz)]
+    conv_args = [dp, vp, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.ss_conv2d_fwd.argtypes = conv_args
+    lib.ss_conv2d_dense_fwd.argtypes = conv_args
+    for name in EXPORTS[1:]:
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def status_string(status: int) -> str:
+    return _lib.ss_status_string(int(status)).decode()
+
+
+def make_desc(cout, cin, kh, kw, dtype=SS_F16, korder=SS_K_CRS) -> ss_weight_desc:
+    return ss_weight_desc(int(cout), int(cin), int(kh), int(kw), int(dtype), int(korder))
+
+
+def _stream_ptr(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_ptr(t, name, dtypes=None, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise SSError(SS_ERR_INVALID_ARG, f"{name} is None")
+    if not t.is_cuda:
+        raise SSError(SS_ERR_INVALID_ARG, f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise SSError(SS_ERR_INVALID_ARG, f"{name} must be contiguous")
+    if dtypes is not None and t.dtype not in dtypes:
+        raise SSError(SS_ERR_INVALID_ARG, f"{name} has dtype {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+_T16 = (torch.float16, torch.bfloat16, torch.int16, torch.uint16)
+
+
+def torch_dtype(dtype: int):
+    return torch.float16 if dtype == SS_F16 else torch.bfloat16
+
+
+def ss_packed_bytes(desc: ss_weight_desc) -> int:
+    out = ctypes.c_size_t(0)
+    st = _lib.ss_packed_bytes(ctypes.byref(desc), ctypes.byref(out))
+    if st != SS_OK:
+        raise SSError(st, "ss_packed_bytes")
+    return int(out.value)
+
+
+def ss_dense_bytes(desc: ss_weight_desc) -> int:
+    out = ctypes.c_size_t(0)
+    st = _lib.ss_dense_bytes(ctypes.byref(desc), ctypes.byref(out))
+    if st != SS_OK:
+        raise SSError(st, "ss_dense_bytes")
+    return int(out.value)
+
+
+def ss_mask_compress(desc: ss_weight_desc, W: torch.Tensor, M: torch.Tensor, packed: torch.Tensor | None = None,
+                     stream=None) -> torch.Tensor:
+    """W [cout, K] 16-bit, M [cout, K] uint8 (device) -> packed uint8 buffer (device)."""
+    K = desc.cin * desc.kh * desc.kw
+    if W is not None and W.numel() != desc.cout * K or M is not None and M.numel() != desc.cout * K:
+        raise SSError(SS_ERR_INVALID_ARG, "ss_mask_compress: W/M size does not match the descriptor")
+    if packed is None:
+        packed = torch.empty(ss_packed_bytes(desc), dtype=torch.uint8, device=W.device)
+    elif packed.numel() * packed.element_size() < ss_packed_bytes(desc):
+        raise SSError(SS_ERR_INVALID_ARG, "ss_mask_compress: packed buffer too small")
+    bad = (ctypes.c_int32 * 2)(-1, -1)
+    st = _lib.ss_mask_compress(ctypes.byref(desc), _dev_ptr(W, "W", _T16), _dev_ptr(M, "M", (torch.uint8, torch.bool)),
+                               _dev_ptr(packed, "packed"), bad, _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_mask_compress", detail=(bad[0], bad[1]) if st == SS_ERR_BAD_MASK else None)
+    return packed
+
+
+def ss_mask_decompress(desc: ss_weight_desc, packed: torch.Tensor, out: torch.Tensor | None = None,
+                       stream=None) -> torch.Tensor:
+    K = desc.cin * desc.kh * desc.kw
+    if out is None:
+        out = torch.empty((desc.cout, K), dtype=torch_dtype(desc.dtype), device=packed.device)
+    st = _lib.ss_mask_decompress(ctypes.byref(desc), _dev_ptr(packed, "packed"), _dev_ptr(out, "out", _T16),
+                                 _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_mask_decompress")
+    return out
+
+
+def ss_dense_pack(desc: ss_weight_desc, W: torch.Tensor, M: torch.Tensor | None, dense: torch.Tensor | None = None,
+                  stream=None) -> torch.Tensor:
+    K = desc.cin * desc.kh * desc.kw
+    if W.numel() != desc.cout * K or (M is not None and M.numel() != desc.cout * K):
+        raise SSError(SS_ERR_INVALID_ARG, "ss_dense_pack: W/M size does not match the descriptor")
+    if dense is None:
+        dense = torch.empty(ss_dense_bytes(desc), dtype=torch.uint8, device=W.device)
+    elif dense.numel() * dense.element_size() < ss_dense_bytes(desc):
+        raise SSError(SS_ERR_INVALID_ARG, "ss_dense_pack: dense buffer too small")
+    st = _lib.ss_dense_pack(ctypes.byref(desc), _dev_ptr(W, "W", _T16),
+                            _dev_ptr(M, "M", (torch.uint8, torch.bool), allow_none=True),
+                            _dev_ptr(dense, "dense"), _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_dense_pack")
+    return dense
+
+
+def ss_conv2d_workspace_bytes(desc, N, H, W, stride=(1, 1), pad=(0, 0)) -> int:
+    out = ctypes.c_size_t(0)
+    st = _lib.ss_conv2d_workspace_bytes(ctypes.byref(desc), N, H, W, stride[0], stride[1], pad[0], pad[1],
+                                        ctypes.byref(out))
+    if st != SS_OK:
+        raise SSError(st, "ss_conv2d_workspace_bytes")
+    return int(out.value)
+
+
+def out_shape(desc, N, H, W, stride=(1, 1), pad=(0, 0)):
+    if stride[0] <= 0 or stride[1] <= 0 or pad[0] < 0 or pad[1] < 0:
+        raise SSError(SS_ERR_INVALID_ARG, "stride must be positive and pad non-negative")
+    Ho = (H + 2 * pad[0] - desc.kh) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - desc.kw) // stride[1] + 1
+    return (N, Ho, Wo, desc.cout)
+
+
+def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream):
+    if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
+    N, H, W, _ = x.shape
+    shp = out_shape(desc, N, H, W, stride, pad)
+    if shp[1] <= 0 or shp[2] <= 0:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != shp or y.dtype != x.dtype:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: y must be {shp} {x.dtype}")
+    need = ss_conv2d_workspace_bytes(desc, N, H, W, stride, pad)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        ws_bytes = need
+    st = fn(ctypes.byref(desc), _dev_ptr(x, "x", (torch_dtype(desc.dtype),)), N, H, W, _dev_ptr(wbuf, "weights"),
+            _dev_ptr(bias, "bias", (torch.float32,), allow_none=True), stride[0], stride[1], pad[0], pad[1], act,
+            _dev_ptr(y, "y"), _dev_ptr(workspace, "workspace", allow_none=True), ws_bytes, _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, what)
+    return y
+
+
+def ss_conv2d_fwd(desc, x, packed, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None, workspace=None,
+                  stream=None) -> torch.Tensor:
+    """2:4-sparse convolution: x NHWC [N,H,W,cin] -> y NHWC [N,Ho,Wo,cout] (same 16-bit dtype)."""
+    return _conv(_lib.ss_conv2d_fwd, "ss_conv2d_fwd", desc, x, packed, bias, stride, pad, act, y, workspace, stream)
+
+
+def ss_conv2d_dense_fwd(desc, x, dense, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
+                        workspace=None, stream=None) -> torch.Tensor:
+    """The dense-MFMA twin on the operand built by ss_dense_pack."""
+    return _conv(_lib.ss_conv2d_dense_fwd, "ss_conv2d_dense_fwd", desc, x, dense, bias, stride, pad, act, y,
+                 workspace, stream)

@@ -1,0 +1,44 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and the
+calls that never touch the device (sizes, status strings, descriptor validation) behave."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def declared_functions():
+    text = (ROOT / "include" / "ss.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ss_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2411_00288_amd as ss
+    lib = ctypes.CDLL(str(ss.LIB_PATH))
+    names = declared_functions()
+    assert len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/ss.h but not exported"
+    assert sorted(ss.EXPORTS) == names
+
+
+def test_size_queries_and_descriptor_validation():
+    import paper_2411_00288_amd as ss
+    d = ss.make_desc(256, 256, 3, 3)
+    assert ss.ss_packed_bytes(d) == 256 + 256 * 2304 + 256 * 2304 // 8       # 9/16 of dense + header
+    assert ss.ss_dense_bytes(d) == 256 + 2 * 256 * 2304
+    assert ss.ss_packed_bytes(ss.make_desc(40, 8, 3, 3)) == 256 + 2 * 3 * 1024 + 2 * 2 * 256
+    assert ss.ss_conv2d_workspace_bytes(d, 32, 14, 14, (1, 1), (1, 1)) >= 0
+    for bad, code in [(ss.make_desc(64, 3, 7, 7), ss.SS_ERR_UNSUPPORTED),       # K = 147
+                      (ss.make_desc(0, 8, 1, 1), ss.SS_ERR_INVALID_ARG),
+                      (ss.make_desc(8, 8, 1, 1, dtype=5), ss.SS_ERR_INVALID_ARG),
+                      (ss.make_desc(8, 8, 1, 1, korder=2), ss.SS_ERR_INVALID_ARG)]:
+        with pytest.raises(ss.SSError) as ei:
+            ss.ss_packed_bytes(bad)
+        assert ei.value.status == code
+    assert ss.ss_dense_bytes(ss.make_desc(64, 3, 7, 7)) == 256 + 2 * 5 * 2048    # dense accepts any K
+    assert "mask" in ss.ss_status_string(ss.SS_ERR_BAD_MASK)
+    assert ss.ss_status_string(0) == "SS_OK"
