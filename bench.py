@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2:4-sparse convolution on one MI355X.
+
+A step is one launch of ss_conv2d_fwd (implicit unfold + sparse contraction + fused bias/ReLU
+epilogue) on the ResNet-50-style 3x3 layer (N=32, 256->256, 14x14, fp16), with every operand
+already resident in device memory; the weight compressor is a one-off per weight update and is
+timed separately.  The dense twin is timed the same way for the speed-up ratio, and the CPU
+oracle is timed on the host cores as a reported baseline.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table]      (--table: per-layer report)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+import numpy as np
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+SPARSE_PEAK_TFLOPS = 5000.0   # 2:4-sparse fp16/bf16 MFMA, dense-equivalent = 2 x the 2.5 PFLOP/s dense peak
+DENSE_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0
+
+
+def _to_dev(bits, dtype, torch, ss):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(ss.torch_dtype(dtype))
+
+
+class LayerRun:
+    """Device-resident operands of one layer and closures that launch the sparse / dense path."""
+
+    def __init__(self, L, torch, ss, wl, copies: int = 1, values: bool = True):
+        self.L = L
+        self.desc = ss.make_desc(L.cout, L.cin, L.kh, L.kw, L.dtype, L.korder)
+        tdt = ss.torch_dtype(L.dtype)
+        if values:
+            d = wl.make_inputs(L)
+            self.host = d
+            W = _to_dev(d["W"], L.dtype, torch, ss)
+            M = None if d["M"] is None else torch.from_numpy(d["M"]).cuda()
+            x0 = _to_dev(d["x"], L.dtype, torch, ss)
+            self.bias = torch.from_numpy(d["bias"]).cuda()
+        else:   # timing only: shapes and value distribution matter, not the exact draw
+            g = torch.Generator(device="cuda").manual_seed(L.seed)
+            W = (torch.randn((L.cout, L.K), generator=g, device="cuda") * (2.0 / L.K) ** 0.5).to(tdt)
+            M = None
+            if L.mask != "none":
+                pat = torch.tensor([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]],
+                                   dtype=torch.uint8, device="cuda")
+                M = pat[torch.randint(0, 6, (L.cout, L.K // 4), generator=g, device="cuda")].reshape(L.cout, L.K).contiguous()
+            x0 = torch.randn((L.N, L.H, L.W, L.cin), generator=g, device="cuda")
+            x0 = (x0.clamp_(min=0) if L.relu_input else x0).to(tdt)
+            self.bias = torch.randn(L.cout, generator=g, device="cuda") * 0.1
+        self.W, self.M = W, M
+        self.packed = ss.ss_mask_compress(self.desc, W, M) if M is not None else None
+        self.dense = ss.ss_dense_pack(self.desc, W, M)
+        self.xs = [x0] + [x0.clone() for _ in range(copies - 1)]
+        st, pd = (L.stride,) * 2, (L.pad,) * 2
+        self.calls_s, self.calls_d, self.ys = [], [], []
+        for xi in self.xs:
+            cd, y = ss.prepare_conv2d(self.desc, xi, self.dense, self.bias, st, pd, L.act, sparse=False)
+            self.calls_d.append(cd)
+            self.ys.append(y)
+            if self.packed is not None:
+                cs, _ = ss.prepare_conv2d(self.desc, xi, self.packed, self.bias, st, pd, L.act, y=y, sparse=True)
+                self.calls_s.append(cs)
+        self.i = 0
+
+    def sparse(self):
+        self.i = (self.i + 1) % len(self.xs)
+        self.calls_s[self.i]()
+
+    def densef(self):
+        self.i = (self.i + 1) % len(self.xs)
+        self.calls_d[self.i]()
+
+
+def time_graph(torch, fn, steps: int, warmup: int) -> float:
+    """Milliseconds per launch with the `steps` launches captured in one HIP graph, so that the
+    host's launch rate does not bound a kernel that runs for a few microseconds."""
+    for _ in range(max(warmup, 1)):
+        fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(steps):
+                fn()
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    time_graph.last_wall_ms = wall_ms / steps
+    return e0.elapsed_time(e1) / steps
+
+
+def time_launches(torch, fn, steps: int, warmup: int) -> float:
+    """Milliseconds per launch: `steps` back-to-back launches between two events on the launch stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def median_time(torch, fn, steps, warmup, reps=5, graph=True):
+    timer = time_graph if graph else time_launches
+    return float(np.median([timer(torch, fn, steps, warmup if r == 0 else 2) for r in range(reps)]))
+
+
+def cpu_baseline(L, wl):
+    """The oracle as it stands, timed once on the host cores on the same workload."""
+    import oracle
+    d = wl.make_inputs(L)
+    t0 = time.perf_counter()
+    oracle.conv2d(d["x"], d["W"], d["M"], cin=L.cin, kh=L.kh, kw=L.kw, korder=L.korder, dtype=L.dtype,
+                  bias=d["bias"], stride=(L.stride,) * 2, pad=(L.pad,) * 2, act=L.act)
+    dt = time.perf_counter() - t0
+    return {"value": L.dense_equiv_flop / dt / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"the full workload ({L.name}: all {L.P * L.cout} outputs), one run, fp64 direct convolution"}
+
+
+def layer_report(torch, ss, wl, L, steps, warmup, cold=False):
+    copies = 1
+    if cold:   # rotate through > 512 MB of distinct activations so nothing stays cache-resident
+        per = 2 * L.N * L.H * L.W * L.cin + 2 * L.P * L.cout
+        copies = max(2, min(64, int(600e6 // per) + 1))
+    run = LayerRun(L, torch, ss, wl, copies=copies, values=False)
+    out = {"layer": L.name, "count": L.count, "gflop": L.dense_equiv_flop / 1e9, "masked": L.mask != "none"}
+    td = median_time(torch, run.densef, steps, warmup, reps=3)
+    out["dense_us"] = td * 1e3
+    if L.mask != "none":
+        ts = median_time(torch, run.sparse, steps, warmup, reps=3)
+        out["sparse_us"] = ts * 1e3
+        out["speedup"] = td / ts
+        out["tflops"] = L.dense_equiv_flop / ts / 1e9
+        out["gbs"] = L.algorithmic_bytes(True) / ts / 1e6
+        out["t_floor_us"] = max(L.dense_equiv_flop / SPARSE_PEAK_TFLOPS / 1e6, L.algorithmic_bytes(True) / HBM_PEAK_GBS / 1e3)
+    else:
+        out["tflops"] = L.dense_equiv_flop / td / 1e9
+        out["gbs"] = L.algorithmic_bytes(False) / td / 1e6
+        out["t_floor_us"] = max(L.dense_equiv_flop / DENSE_PEAK_TFLOPS / 1e6, L.algorithmic_bytes(False) / HBM_PEAK_GBS / 1e3)
+    del run
+    torch.cuda.empty_cache()
+    return out
+
+
+def print_table(torch, ss, wl, steps, warmup, cold, only=""):
+    rows = []
+    groups = [("configs 0-2", [wl.CONFIG0, wl.CONFIG1, wl.CONFIG2]), ("ResNet-50 conv stack, batch 64, bf16", wl.resnet50_layers()),
+              ("ConvNeXt-T stage 1, batch 128, bf16", wl.convnext_t_stage1_layers())]
+    for title, layers in groups:
+        layers = [L for L in layers if only in L.name]
+        if not layers:
+            continue
+        print(f"## {title}" + (" (cold: rotating buffers)" if cold else " (warm: buffers reused)"), flush=True)
+        print(f"{'layer':34s} {'x':>2s} {'GFLOP':>8s} {'sparse us':>10s} {'dense us':>9s} {'speedup':>7s} {'TFLOP/s':>8s} {'GB/s':>7s} {'floor us':>8s} {'frac':>5s}")
+        tot_s = tot_d = tot_f = 0.0
+        for L in layers:
+            r = layer_report(torch, ss, wl, L, steps, warmup, cold)
+            rows.append(r)
+            t_used = r.get("sparse_us", r["dense_us"])
+            tot_s += L.count * t_used
+            tot_d += L.count * r["dense_us"]
+            tot_f += L.count * r["t_floor_us"]
+            print(f"{L.name:34s} {L.count:2d} {r['gflop']:8.2f} {r.get('sparse_us', float('nan')):10.2f} {r['dense_us']:9.2f} "
+                  f"{r.get('speedup', float('nan')):7.2f} {r['tflops']:8.1f} {r['gbs']:7.0f} {r['t_floor_us']:8.2f} {r['t_floor_us'] / t_used:5.2f}", flush=True)
+        print(f"{'total (x count)':34s}    {'':8s} {tot_s:10.1f} {tot_d:9.1f} {tot_d / tot_s:7.2f} {'':8s} {'':7s} {tot_f:8.1f} {tot_f / tot_s:5.2f}", flush=True)
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--table", action="store_true", help="per-layer report for all configurations instead of the JSON line")
+    ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
+    ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the method has no multi-GPU path; batch sharding needs no "
+              "exchange). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2411_00288_amd as ss
+    from paper_2411_00288_amd import workloads as wl
+    torch.cuda.set_device(0)
+
+    if args.table:
+        print_table(torch, ss, wl, args.steps, args.warmup, args.cold, args.only)
+        return
+
+    L = wl.CONFIG1
+    run = LayerRun(L, torch, ss, wl)
+
+    # ---- the timed region: exactly `steps` launches of the sparse convolution, recorded in one HIP
+    # graph (a launch lasts a few microseconds, less than the host needs to issue one), replayed
+    # once between two events on the launch stream and bracketed by device synchronisation.
+    kern_ms = time_graph(torch, run.sparse, args.steps, args.warmup)
+    ms = max(kern_ms, time_graph.last_wall_ms)
+    value = L.dense_equiv_flop / ms / 1e9              # dense-equivalent TFLOP/s
+    eager_ms = time_launches(torch, run.sparse, args.steps, 2)   # host-issued launches, for reference
+
+    # ---- companions (not part of `value`)
+    t_dense = median_time(torch, run.densef, args.steps, args.warmup)
+    t_sparse = median_time(torch, run.sparse, args.steps, 2)
+    Lbig = wl.with_batch(L, 512)                      # same layer, 16x the batch: asymptotic utilisation
+    big = LayerRun(Lbig, torch, ss, wl, values=False)
+    tb_s = median_time(torch, big.sparse, 20, 3, reps=3)
+    tb_d = median_time(torch, big.densef, 20, 3, reps=3)
+    del big
+    tc = time_launches(torch, lambda: ss.ss_mask_compress(run.desc, run.W, run.M, packed=run.packed), 20, 3)
+
+    achieved = L.dense_equiv_flop / kern_ms / 1e9
+    out = {
+        "metric": "dense-equiv TFLOP/s of 2:4 sparse conv2d; speedup vs same-design dense conv",
+        "value": value, "unit": "TFLOP/s (dense-equivalent)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: 3x3 conv 256->256, 14x14, N=32, stride 1, pad 1, fp16 NHWC, "
+                               "argmax-of-logits 2:4 mask along Cin*kh*kw, fused bias+ReLU", "K": L.K, "P": L.P},
+        "speedup_vs_dense_twin": t_dense / t_sparse,
+        "sparse_us": t_sparse * 1e3, "dense_twin_us": t_dense * 1e3,
+        "scaled_batch": {"workload": "same layer at N=512", "sparse_us": tb_s * 1e3, "dense_twin_us": tb_d * 1e3,
+                         "tflops": Lbig.dense_equiv_flop / tb_s / 1e9, "speedup": tb_d / tb_s,
+                         "frac_sparse_peak": Lbig.dense_equiv_flop / tb_s / 1e9 / SPARSE_PEAK_TFLOPS},
+        "compress_us": tc * 1e3, "eager_launch_us": eager_ms * 1e3,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "ss::conv_kernel (sparse, fp16)", "flop_per_launch": L.dense_equiv_flop,
+                     "kernel_us": kern_ms * 1e3},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(L, wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

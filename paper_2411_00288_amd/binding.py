@@ -177,7 +177,7 @@ def out_shape(desc, N, H, W, stride=(1, 1), pad=(0, 0)):
     return (N, Ho, Wo, desc.cout)
 
 
-def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream):
+def _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream):
     if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
     N, H, W, _ = x.shape
@@ -193,12 +193,36 @@ def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream)
     if need > 0 and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         ws_bytes = need
-    st = fn(ctypes.byref(desc), _dev_ptr(x, "x", (torch_dtype(desc.dtype),)), N, H, W, _dev_ptr(wbuf, "weights"),
+    args = (ctypes.byref(desc), _dev_ptr(x, "x", (torch_dtype(desc.dtype),)), N, H, W, _dev_ptr(wbuf, "weights"),
             _dev_ptr(bias, "bias", (torch.float32,), allow_none=True), stride[0], stride[1], pad[0], pad[1], act,
-            _dev_ptr(y, "y"), _dev_ptr(workspace, "workspace", allow_none=True), ws_bytes, _stream_ptr(stream))
+            _dev_ptr(y, "y"), _dev_ptr(workspace, "workspace", allow_none=True), ws_bytes)
+    return args, y, workspace
+
+
+def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream):
+    args, y, _ws = _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream)
+    st = fn(*args, _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, what)
     return y
+
+
+def prepare_conv2d(desc, x, wbuf, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None, workspace=None,
+                   sparse=True):
+    """Marshal the arguments of ss_conv2d_fwd / ss_conv2d_dense_fwd once and return (launch, y):
+    ``launch()`` enqueues the call on the current torch stream.  For launch-bound loops and graph
+    capture, where per-call Python argument checking would dominate.  The tensors passed here
+    must stay alive and in place for as long as ``launch`` is used."""
+    fn = _lib.ss_conv2d_fwd if sparse else _lib.ss_conv2d_dense_fwd
+    what = "ss_conv2d_fwd" if sparse else "ss_conv2d_dense_fwd"
+    args, y, ws = _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, None)
+    keep = (desc, x, wbuf, bias, y, ws)
+
+    def launch(_keep=keep):
+        st = fn(*args, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != SS_OK:
+            raise SSError(st, what)
+    return launch, y
 
 
 def ss_conv2d_fwd(desc, x, packed, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None, workspace=None,

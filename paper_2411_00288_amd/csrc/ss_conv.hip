@@ -38,8 +38,6 @@ struct ConvParams {
     int tiles_m;
 };
 
-enum { MODE_VEC = 0, MODE_GATHER = 1 };
-
 template <int DT, int ABID>
 __device__ __forceinline__ f32x16 mma_sparse(uint4 a, const B32 &b, f32x16 c, uint32_t idx)
 {
@@ -72,22 +70,38 @@ __device__ __forceinline__ uint32_t cvt_pack2(float a, float b)
     }
 }
 
-// Weight fragments of one reduction chunk (KSTEPS steps) for the TM row tiles of a wave.
-template <bool SPARSE, int KSTEPS, int TM>
-struct AFrag {
-    uint4 v[KSTEPS][SPARSE ? 1 : 2][TM];
-    uint32_t idx[(KSTEPS + 1) / 2][TM];
+// How the [pixels x reduction-chunk] slice of the unfolded input is built in LDS:
+//   MODE_VEC    channels are contiguous inside every aligned run of 8 reduction indices (1x1
+//               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads.
+//   MODE_GATHER any flattening / shape: one 16-bit load per element.
+//   MODE_TAPS   the paper's flattening (channel slowest) with a KH x KW kernel and cin % 4 == 0:
+//               a 2:4 block then holds 4 consecutive (channel, tap) pairs, i.e. activations of
+//               different pixels.  A thread loads, for one output pixel and 4 channels, the
+//               KH*KW taps as 8-byte channel vectors and transposes them in registers to
+//               channel-major order before the LDS write, so the MFMA side still reads 16-byte
+//               vectors.  A chunk is 32 channels = KH*KW reduction steps.
+enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2 };
+
+// Weight fragments of one 32-wide reduction step for the TM row tiles of a wave.
+template <bool SPARSE, int TM>
+struct AStep {
+    uint4 v[SPARSE ? 1 : 2][TM];
+    uint32_t idx[TM];
 };
 
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE>
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams p)
 {
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int BM = WAVES_M * TM * 32;
     constexpr int BN = WAVES_N * TN * 32;
-    constexpr int KSTEPS = 2;
+    constexpr int TAPS = KH * KW;
+    constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : 2;    // 32-wide reduction steps per LDS chunk
+    constexpr int RING = (KSTEPS % 3 == 0) ? 3 : ((KSTEPS % 4 == 0) ? 4 : 2);   // weight prefetch ring, divides KSTEPS
+    constexpr int PF = RING - 1;
+    static_assert(KSTEPS % RING == 0, "ring must divide the chunk");
     constexpr int BK = KSTEPS * 32;
-    constexpr int ROW = BK + 8;          // +16 bytes: consecutive pixels land 9 x 16 bytes apart -> conflict-free b128 reads
+    constexpr int ROW = BK + 8;          // +16 bytes per pixel row: 16-byte LDS reads of 16 consecutive pixels hit distinct banks
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t *Bs0 = smem;
     uint16_t *Bs1 = smem + BN * ROW;
@@ -104,7 +118,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
     const int HoWo = p.Ho * p.Wo;
 
     // ------------------------------------------------------------------ activation staging state
-    constexpr int UNITS = (MODE == MODE_VEC) ? 8 : 16;     // 16-byte chunks or 4-element blocks per pixel row
+    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : 8;   // per pixel row and chunk: 4-element blocks / 16-byte runs / 4-channel bricks
     constexpr int ITEMS = BN * UNITS / NT;
     static_assert(BN * UNITS % NT == 0 && NT % UNITS == 0, "tile/threads mismatch");
     const int unit = tid % UNITS;
@@ -127,7 +141,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
             pixoff[i] = 0;
         }
     }
-    // MODE_VEC: position of this thread's 8-element chunk in the (tap, channel) space
+    // MODE_VEC: position of this thread's 8-element run in the (tap, channel) space
     int vk = unit * 8, vc = 0, vr = 0, vt = 0;
     if constexpr (MODE == MODE_VEC) {
         int tap = vk / p.Cin;
@@ -138,10 +152,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 
     uint4 stage_v[MODE == MODE_VEC ? ITEMS : 1];
     uint16_t stage_g[MODE == MODE_GATHER ? ITEMS : 1][4];
+    uint2 stage_t[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
-    auto stage_load = [&](int k0) {
+    auto stage_load = [&](int ci) {
         if constexpr (MODE == MODE_VEC) {
-            (void)k0;
 #pragma unroll
             for (int i = 0; i < ITEMS; i++) {
                 int ih = ih0[i] + vr, iw = iw0[i] + vt;
@@ -156,12 +170,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
                 vc -= p.Cin;
                 if (++vt == p.kw) { vt = 0; ++vr; }
             }
-        } else {
+        } else if constexpr (MODE == MODE_GATHER) {
             int off[4], er[4], et[4];
             bool kok[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                int k = k0 + unit * 4 + e;
+                int k = ci * BK + unit * 4 + e;
                 kok[e] = k < p.K;
                 int c, r, t;
                 if (p.korder == SS_K_CRS) {
@@ -189,6 +203,21 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
                     stage_g[i][e] = ok ? p.x[pixoff[i] + off[e]] : (uint16_t)0;
                 }
             }
+        } else {
+            const int cb = ci * 32 + unit * 4;          // first of this thread's 4 channels
+            const bool cok = cb < p.Cin;
+#pragma unroll
+            for (int i = 0; i < ITEMS; i++) {
+#pragma unroll
+                for (int tap = 0; tap < TAPS; tap++) {
+                    const int r = tap / KW, t = tap % KW;
+                    int ih = ih0[i] + r, iw = iw0[i] + t;
+                    bool ok = cok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                    uint2 v = make_uint2(0, 0);
+                    if (ok) v = *reinterpret_cast<const uint2 *>(p.x + (pixoff[i] + (r * p.W + t) * p.Cin + cb));
+                    stage_t[i][tap] = v;
+                }
+            }
         }
     };
     auto stage_store = [&](uint16_t *Bs) {
@@ -197,48 +226,52 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
             int pr = tid / UNITS + i * (NT / UNITS);
             if constexpr (MODE == MODE_VEC) {
                 *reinterpret_cast<uint4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
-            } else {
+            } else if constexpr (MODE == MODE_GATHER) {
                 uint2 v = make_uint2((uint32_t)stage_g[i][0] | ((uint32_t)stage_g[i][1] << 16),
                                      (uint32_t)stage_g[i][2] | ((uint32_t)stage_g[i][3] << 16));
                 *reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * 4) = v;
+            } else {
+                // [tap][4 channels] -> [channel][tap]: output element h = c*TAPS + tap, two per dword
+                uint32_t o[2 * TAPS];
+#pragma unroll
+                for (int d = 0; d < 2 * TAPS; d++) {
+                    const int ha = 2 * d, hb = 2 * d + 1;
+                    const int ca = ha / TAPS, ta = ha % TAPS, cbn = hb / TAPS, tb = hb % TAPS;
+                    uint32_t sa = (ca < 2) ? stage_t[i][ta].x : stage_t[i][ta].y;
+                    uint32_t sb = (cbn < 2) ? stage_t[i][tb].x : stage_t[i][tb].y;
+                    const uint32_t sel = (uint32_t)(2 * (ca & 1)) | ((uint32_t)(2 * (ca & 1) + 1) << 8) |
+                                         ((uint32_t)(4 + 2 * (cbn & 1)) << 16) | ((uint32_t)(5 + 2 * (cbn & 1)) << 24);
+                    o[d] = __builtin_amdgcn_perm(sb, sa, sel);
+                }
+                uint2 *dst = reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * (4 * TAPS));
+#pragma unroll
+                for (int d = 0; d < TAPS; d++) dst[d] = make_uint2(o[2 * d], o[2 * d + 1]);
             }
         }
     };
 
     // ------------------------------------------------------------------ weight fragments
     const int mt0 = (m0 >> 5) + wm * TM;
-    auto load_a = [&](AFrag<SPARSE, KSTEPS, TM> &a, int ks0) {
+    auto load_a = [&](AStep<SPARSE, TM> &a, int ks) {
 #pragma unroll
-        for (int s = 0; s < KSTEPS; s++) {
-            int ks = ks0 + s;
-#pragma unroll
-            for (int tm = 0; tm < TM; tm++) {
-                int mt = mt0 + tm;
-                bool ok = ks < p.Ks && mt < p.Mt;
-                if constexpr (SPARSE) {
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (ok) v = *reinterpret_cast<const uint4 *>(p.a_vals + (((size_t)mt * p.Ks + ks) * 64 + lane) * 16);
-                    a.v[s][0][tm] = v;
-                } else {
-#pragma unroll
-                    for (int h = 0; h < 2; h++) {
-                        uint4 v = make_uint4(0, 0, 0, 0);
-                        if (ok) v = *reinterpret_cast<const uint4 *>(p.a_vals + ((((size_t)mt * p.Ks + ks) * 2 + h) * 64 + lane) * 16);
-                        a.v[s][h][tm] = v;
-                    }
+        for (int tm = 0; tm < TM; tm++) {
+            int mt = mt0 + tm;
+            bool ok = ks < p.Ks && mt < p.Mt;
+            if constexpr (SPARSE) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                uint32_t w = 0x44444444u;
+                if (ok) {
+                    v = *reinterpret_cast<const uint4 *>(p.a_vals + (((size_t)mt * p.Ks + ks) * 64 + lane) * 16);
+                    w = p.a_meta[((size_t)mt * p.Kp + (ks >> 1)) * 64 + lane];
                 }
-            }
-        }
-        if constexpr (SPARSE) {
+                a.v[0][tm] = v;
+                a.idx[tm] = (ks & 1) ? (w >> 16) : w;    // the instruction reads index bits [15:0]
+            } else {
 #pragma unroll
-            for (int sp = 0; sp < (KSTEPS + 1) / 2; sp++) {
-                int kp = (ks0 >> 1) + sp;
-#pragma unroll
-                for (int tm = 0; tm < TM; tm++) {
-                    int mt = mt0 + tm;
-                    uint32_t w = 0x44444444u;
-                    if (kp < p.Kp && mt < p.Mt) w = p.a_meta[((size_t)mt * p.Kp + kp) * 64 + lane];
-                    a.idx[sp][tm] = w;
+                for (int h = 0; h < 2; h++) {
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (ok) v = *reinterpret_cast<const uint4 *>(p.a_vals + ((((size_t)mt * p.Ks + ks) * 2 + h) * 64 + lane) * 16);
+                    a.v[h][tm] = v;
                 }
             }
         }
@@ -252,51 +285,43 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 #pragma unroll
             for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0.f;
 
-    auto compute = [&](const uint16_t *Bs, const AFrag<SPARSE, KSTEPS, TM> &a) {
+    // ------------------------------------------------------------------ main loop (double-buffered LDS, ring of weight steps)
+    const int nchunks = (p.Ks + KSTEPS - 1) / KSTEPS;
+    AStep<SPARSE, TM> a[RING];
+    stage_load(0);
+#pragma unroll
+    for (int s = 0; s < PF; s++) load_a(a[s], s);
+    stage_store(Bs0);
+    __syncthreads();
+    for (int ci = 0; ci < nchunks; ci++) {
+        const uint16_t *cur = (ci & 1) ? Bs1 : Bs0;
+        uint16_t *nxt = (ci & 1) ? Bs0 : Bs1;
+        const bool more = ci + 1 < nchunks;
+        if (more) stage_load(ci + 1);
 #pragma unroll
         for (int s = 0; s < KSTEPS; s++) {
+            load_a(a[(s + PF) % RING], ci * KSTEPS + s + PF);
             B32 b[TN];
 #pragma unroll
             for (int tn = 0; tn < TN; tn++) {
-                const uint16_t *src = Bs + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
+                const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
                 b[tn].lo = *reinterpret_cast<const uint4 *>(src);
                 b[tn].hi = *reinterpret_cast<const uint4 *>(src + 8);
             }
+            const AStep<SPARSE, TM> &as = a[s % RING];
 #pragma unroll
             for (int tm = 0; tm < TM; tm++)
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
                     if constexpr (SPARSE) {
-                        if (s & 1) acc[tm][tn] = mma_sparse<DT, 1>(a.v[s][0][tm], b[tn], acc[tm][tn], a.idx[s >> 1][tm]);
-                        else       acc[tm][tn] = mma_sparse<DT, 0>(a.v[s][0][tm], b[tn], acc[tm][tn], a.idx[s >> 1][tm]);
+                        acc[tm][tn] = mma_sparse<DT, 0>(as.v[0][tm], b[tn], acc[tm][tn], as.idx[tm]);
                     } else {
-                        acc[tm][tn] = mma_dense<DT>(a.v[s][0][tm], b[tn].lo, acc[tm][tn]);
-                        acc[tm][tn] = mma_dense<DT>(a.v[s][1][tm], b[tn].hi, acc[tm][tn]);
+                        acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[tn].lo, acc[tm][tn]);
+                        acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[tn].hi, acc[tm][tn]);
                     }
                 }
         }
-    };
-
-    // ------------------------------------------------------------------ main loop (double-buffered LDS)
-    const int nchunks = (p.Ks + KSTEPS - 1) / KSTEPS;
-    AFrag<SPARSE, KSTEPS, TM> a_cur, a_nxt;
-    stage_load(0);
-    load_a(a_cur, 0);
-    stage_store(Bs0);
-    __syncthreads();
-    for (int ci = 0; ci < nchunks; ci++) {
-        uint16_t *cur = (ci & 1) ? Bs1 : Bs0;
-        uint16_t *nxt = (ci & 1) ? Bs0 : Bs1;
-        const bool more = ci + 1 < nchunks;
-        if (more) {
-            stage_load((ci + 1) * BK);
-            load_a(a_nxt, (ci + 1) * KSTEPS);
-        }
-        compute(cur, a_cur);
-        if (more) {
-            stage_store(nxt);
-            a_cur = a_nxt;
-        }
+        if (more) stage_store(nxt);
         __syncthreads();
     }
 
@@ -338,33 +363,58 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE>
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr int ROW = 2 * 32 + 8;
+    constexpr int KSTEPS = (MODE == MODE_TAPS) ? KH * KW : 2;
+    constexpr int ROW = KSTEPS * 32 + 8;
     constexpr size_t smem = (size_t)2 * BN * ROW * sizeof(uint16_t);
+    static_assert(smem <= 160 * 1024, "LDS tile too large");
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
-    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE>;
-    if (smem > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return SS_ERR_HIP;
+    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW>;
+    if (smem > 64 * 1024) {
+        static bool attr_set = false;    // once per process: raises this kernel's dynamic-LDS limit
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)smem) != hipSuccess)
+                return SS_ERR_HIP;
+            attr_set = true;
+        }
     }
     kern<<<dim3((unsigned)blocks), dim3(WAVES_M * WAVES_N * 64), smem, s>>>(p);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
 }
 
-template <int DT, bool SPARSE, int MODE>
+template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
     // Enough workgroups to cover the 256 compute units decides the tile size.
     long long big = (long long)((p.Cout + 127) / 128) * ((p.P + 127) / 128);
-    if (p.Cout > 64 && big >= 256) return launch<DT, SPARSE, 2, 2, 2, 2, MODE>(p, s);
-    return launch<DT, SPARSE, 2, 2, 1, 1, MODE>(p, s);
+    if constexpr (MODE == MODE_TAPS && KH * KW > 4) {
+        // a 128-pixel tile of the 3x3 unfold does not fit LDS twice: 128 x 64 is the large shape
+        if (p.Cout > 64 && big >= 128) return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
+    } else {
+        if (p.Cout > 64 && big >= 256) return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
+    }
+    return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
+}
+
+template <int DT, bool SPARSE>
+static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_t s)
+{
+    const int taps = desc->kh * desc->kw;
+    // channels contiguous inside every aligned run of 8 reduction indices?
+    if ((desc->cin % 8 == 0) && (desc->korder == SS_K_RSC || taps == 1)) return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
+    if (desc->korder == SS_K_CRS && desc->cin % 4 == 0) {
+        if (desc->kh == 3 && desc->kw == 3) return pick_tile<DT, SPARSE, MODE_TAPS, 3, 3>(p, s);
+        if (desc->kh == 2 && desc->kw == 2) return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);
+    }
+    return pick_tile<DT, SPARSE, MODE_GATHER, 1, 1>(p, s);
 }
 
 template <bool SPARSE>
@@ -403,13 +453,7 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.K = t.K; p.Ks = t.Ks; p.Kp = t.Kp; p.Mt = t.Mt; p.act = act; p.korder = desc->korder;
     p.tiles_m = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // channels contiguous inside every 8-element chunk of the reduction index?
-    bool vec = (desc->cin % 8 == 0) && (desc->korder == SS_K_RSC || desc->kh * desc->kw == 1);
-    if (desc->dtype == SS_F16) {
-        return vec ? pick_tile<SS_F16, SPARSE, MODE_VEC>(p, s) : pick_tile<SS_F16, SPARSE, MODE_GATHER>(p, s);
-    } else {
-        return vec ? pick_tile<SS_BF16, SPARSE, MODE_VEC>(p, s) : pick_tile<SS_BF16, SPARSE, MODE_GATHER>(p, s);
-    }
+    return desc->dtype == SS_F16 ? pick_mode<SS_F16, SPARSE>(desc, p, s) : pick_mode<SS_BF16, SPARSE>(desc, p, s);
 }
 
 }  // namespace ss

@@ -144,3 +144,33 @@ def test_argument_errors(ss):
         ss.ss_conv2d_fwd(ss.make_desc(8, 16, 3, 3), x, packed, None, (1, 1), (1, 1), 0)
     with pytest.raises(ss.SSError):                    # host tensor
         ss.ss_conv2d_fwd(desc, x.cpu(), packed, None, (1, 1), (1, 1), 0)
+
+
+def test_prepared_launch_in_hip_graph_replays_correctly(ss):
+    # The benchmark records launches in a HIP graph.  Replay several times with eager work and
+    # synchronisation in between, on changing input contents, and compare with the eager result.
+    L = L_(2, 14, 14, 64, 96, 3, p=1)
+    d = wl.make_inputs(L)
+    desc = layer_desc(ss, L)
+    x = dev_bits(d["x"], L.dtype)
+    packed = ss.ss_mask_compress(desc, dev_bits(d["W"], L.dtype), torch.from_numpy(d["M"]).cuda())
+    bias = torch.from_numpy(d["bias"]).cuda()
+    launch, y = ss.prepare_conv2d(desc, x, packed, bias, (1, 1), (1, 1), L.act)
+    launch()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            launch()
+            launch()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x.copy_(torch.roll(x, shifts=rep + 1, dims=2))          # new contents, same buffer
+        eager = ss.ss_conv2d_fwd(desc, x, packed, bias, (1, 1), (1, 1), L.act)
+        torch.cuda.synchronize()
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
