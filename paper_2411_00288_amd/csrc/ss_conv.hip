@@ -12,8 +12,12 @@
 //   One 32x32x32 sparse MFMA consumes, per lane l: 8 kept weights of row l%32 (+16 index bits)
 //   and the 16 activations k = 16*(l/32) + [0,16) of pixel l%32; it leaves rows
 //   8*(v/4) + 4*(l/32) + v%4, v = 0..15, of column l%32 in the lane's 16 accumulators, i.e. runs
-//   of 4 consecutive output channels of one pixel: an 8-byte NHWC store.
+//   of 4 consecutive output channels of one pixel.
 //   The dense twin issues two 32x32x16 dense MFMAs on the same B registers instead.
+//
+// All global reads of activations and weights are raw buffer loads: a lane whose element lies in
+// the zero padding, past the last pixel or past the reduction length presents an offset beyond the
+// buffer's size and the hardware returns 0 -- no branches, no selects.
 #include "ss_internal.h"
 
 namespace ss {
@@ -23,9 +27,10 @@ typedef _Float16 f16x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct B32 {   // one lane's B fragment for a 32-wide reduction step: 16 x 16-bit
-    uint4 lo, hi;
+    u32x4 lo, hi;
 };
 
 struct ConvParams {
@@ -36,21 +41,25 @@ struct ConvParams {
     uint16_t *y;
     int N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, Ho, Wo, P, K, Ks, Kp, Mt, act, korder;
     int tiles_m;
+    unsigned x_bytes, a_bytes, meta_bytes;
 };
 
-template <int DT, int ABID>
-__device__ __forceinline__ f32x16 mma_sparse(uint4 a, const B32 &b, f32x16 c, uint32_t idx)
+constexpr unsigned kOutOfRange = 0x80000000u;   // >= any buffer size used here: the load returns 0
+constexpr int kRsrcFlags = 0x00020000;          // raw buffer, 32-bit data format (gfx9 family)
+
+template <int DT>
+__device__ __forceinline__ f32x16 mma_sparse(u32x4 a, const B32 &b, f32x16 c, uint32_t idx)
 {
     if constexpr (DT == SS_F16)
         return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x16, b), c,
-                                                         (int)idx, 0, ABID);
+                                                         (int)idx, 0, 0);
     else
         return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x16, b), c,
-                                                          (int)idx, 0, ABID);
+                                                          (int)idx, 0, 0);
 }
 
 template <int DT>
-__device__ __forceinline__ f32x16 mma_dense(uint4 a, uint4 b, f32x16 c)
+__device__ __forceinline__ f32x16 mma_dense(u32x4 a, u32x4 b, f32x16 c)
 {
     if constexpr (DT == SS_F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
@@ -72,12 +81,13 @@ __device__ __forceinline__ uint32_t cvt_pack2(float a, float b)
 
 // How the [pixels x reduction-chunk] slice of the unfolded input is built in LDS:
 //   MODE_VEC    channels are contiguous inside every aligned run of 8 reduction indices (1x1
-//               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads.
-//   MODE_GATHER any flattening / shape: one 16-bit load per element.
-//   MODE_TAPS   the paper's flattening (channel slowest) with a KH x KW kernel and cin % 4 == 0:
+//               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads,
+//               chunks of 64 reduction indices.
+//   MODE_GATHER any flattening / shape: one 16-bit load per element (slow, general fallback).
+//   MODE_TAPS   the paper's flattening (channel slowest) with a KH x KW kernel and cin % 32 == 0:
 //               a 2:4 block then holds 4 consecutive (channel, tap) pairs, i.e. activations of
-//               different pixels.  A thread loads, for one output pixel and 4 channels, the
-//               KH*KW taps as 8-byte channel vectors and transposes them in registers to
+//               different pixels.  A thread loads, for one output pixel and 8 channels, the
+//               KH*KW taps as 16-byte channel vectors and transposes them in registers to
 //               channel-major order before the LDS write, so the MFMA side still reads 16-byte
 //               vectors.  A chunk is 32 channels = KH*KW reduction steps.
 enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2 };
@@ -85,23 +95,40 @@ enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2 };
 // Weight fragments of one 32-wide reduction step for the TM row tiles of a wave.
 template <bool SPARSE, int TM>
 struct AStep {
-    uint4 v[SPARSE ? 1 : 2][TM];
+    u32x4 v[SPARSE ? 1 : 2][TM];
     uint32_t idx[TM];
 };
+
+template <int MODE, int KH, int KW>
+struct ChunkShape {
+    static constexpr int TAPS = KH * KW;
+    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : 2;   // 32-wide reduction steps per LDS chunk
+    static constexpr int BK = KSTEPS * 32;
+    static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
+};
+
+template <int BM, int BN, int MODE, int KH, int KW>
+constexpr size_t smem_bytes()
+{
+    size_t stage = (size_t)2 * BN * ChunkShape<MODE, KH, KW>::ROW * 2;
+    size_t epi = (size_t)BN * (BM * 2 + 8);
+    return stage > epi ? stage : epi;
+}
 
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams p)
 {
+    using CS = ChunkShape<MODE, KH, KW>;
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int BM = WAVES_M * TM * 32;
     constexpr int BN = WAVES_N * TN * 32;
-    constexpr int TAPS = KH * KW;
-    constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : 2;    // 32-wide reduction steps per LDS chunk
+    constexpr int TAPS = CS::TAPS;
+    constexpr int KSTEPS = CS::KSTEPS;
     constexpr int RING = (KSTEPS % 3 == 0) ? 3 : ((KSTEPS % 4 == 0) ? 4 : 2);   // weight prefetch ring, divides KSTEPS
     constexpr int PF = RING - 1;
     static_assert(KSTEPS % RING == 0, "ring must divide the chunk");
-    constexpr int BK = KSTEPS * 32;
-    constexpr int ROW = BK + 8;          // +16 bytes per pixel row: 16-byte LDS reads of 16 consecutive pixels hit distinct banks
+    constexpr int BK = CS::BK;
+    constexpr int ROW = CS::ROW;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t *Bs0 = smem;
     uint16_t *Bs1 = smem + BN * ROW;
@@ -117,12 +144,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
     const int n0 = tile_n * BN;
     const int HoWo = p.Ho * p.Wo;
 
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.x), 0, (int)p.x_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a_vals), 0, (int)p.a_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a_meta), 0, (int)p.meta_bytes, kRsrcFlags);
+
     // ------------------------------------------------------------------ activation staging state
-    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : 8;   // per pixel row and chunk: 4-element blocks / 16-byte runs / 4-channel bricks
+    // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
+    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : 8);
     constexpr int ITEMS = BN * UNITS / NT;
-    static_assert(BN * UNITS % NT == 0 && NT % UNITS == 0, "tile/threads mismatch");
+    static_assert(BN * UNITS % NT == 0 && NT % UNITS == 0 && ITEMS >= 1, "tile/threads mismatch");
     const int unit = tid % UNITS;
-    int pixoff[ITEMS], ih0[ITEMS], iw0[ITEMS];
+    unsigned pixbyte[ITEMS];          // byte offset of x[n, ho*sh-ph, wo*sw-pw, 0] (wraps below 0 for padded pixels)
+    int ih0[ITEMS], iw0[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; i++) {
         int pr = tid / UNITS + i * (NT / UNITS);
@@ -134,13 +167,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
             int wo = rem - ho * p.Wo;
             ih0[i] = ho * p.sh - p.ph;
             iw0[i] = wo * p.sw - p.pw;
-            pixoff[i] = ((n * p.H + ih0[i]) * p.W + iw0[i]) * p.Cin;
+            pixbyte[i] = (unsigned)(((n * p.H + ih0[i]) * p.W + iw0[i]) * p.Cin * 2);
         } else {
             ih0[i] = -(1 << 28);     // every bounds test fails -> zeros
             iw0[i] = -(1 << 28);
-            pixoff[i] = 0;
+            pixbyte[i] = 0;
         }
     }
+
     // MODE_VEC: position of this thread's 8-element run in the (tap, channel) space
     int vk = unit * 8, vc = 0, vr = 0, vt = 0;
     if constexpr (MODE == MODE_VEC) {
@@ -149,20 +183,34 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
         vr = tap / p.kw;
         vt = tap - vr * p.kw;
     }
+    // MODE_TAPS: per (pixel, tap) byte offsets, fixed for the whole reduction; the chunk's channel
+    // offset travels in the scalar offset of the load.  Out-of-image taps are out of range for good.
+    unsigned tapoff[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
+    if constexpr (MODE == MODE_TAPS) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; i++)
+#pragma unroll
+            for (int tap = 0; tap < TAPS; tap++) {
+                const int r = tap / KW, t = tap % KW;
+                int ih = ih0[i] + r, iw = iw0[i] + t;
+                bool ok = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                tapoff[i][tap] = ok ? pixbyte[i] + (unsigned)(((r * p.W + t) * p.Cin + unit * 8) * 2) : kOutOfRange;
+            }
+    }
 
-    uint4 stage_v[MODE == MODE_VEC ? ITEMS : 1];
+    u32x4 stage_v[MODE == MODE_VEC ? ITEMS : 1];
     uint16_t stage_g[MODE == MODE_GATHER ? ITEMS : 1][4];
-    uint2 stage_t[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
+    u32x4 stage_t[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
     auto stage_load = [&](int ci) {
         if constexpr (MODE == MODE_VEC) {
+            const unsigned koff = vk < p.K ? (unsigned)(((vr * p.W + vt) * p.Cin + vc) * 2) : kOutOfRange;
 #pragma unroll
             for (int i = 0; i < ITEMS; i++) {
                 int ih = ih0[i] + vr, iw = iw0[i] + vt;
-                bool ok = vk < p.K && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (ok) v = *reinterpret_cast<const uint4 *>(p.x + (pixoff[i] + (vr * p.W + vt) * p.Cin + vc));
-                stage_v[i] = v;
+                bool ok = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W && koff != kOutOfRange;
+                unsigned off = ok ? pixbyte[i] + koff : kOutOfRange;
+                stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
             }
             vk += BK;
             vc += BK;
@@ -171,12 +219,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
                 if (++vt == p.kw) { vt = 0; ++vr; }
             }
         } else if constexpr (MODE == MODE_GATHER) {
-            int off[4], er[4], et[4];
-            bool kok[4];
+            unsigned off[4];
+            int er[4], et[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 int k = ci * BK + unit * 4 + e;
-                kok[e] = k < p.K;
                 int c, r, t;
                 if (p.korder == SS_K_CRS) {
                     int khw = p.kh * p.kw;
@@ -190,34 +237,27 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
                     r = tap / p.kw;
                     t = tap - r * p.kw;
                 }
-                er[e] = r;
+                er[e] = k < p.K ? r : (1 << 29);      // past the reduction length: fails the bounds test
                 et[e] = t;
-                off[e] = (r * p.W + t) * p.Cin + c;
+                off[e] = (unsigned)(((r * p.W + t) * p.Cin + c) * 2);
             }
 #pragma unroll
             for (int i = 0; i < ITEMS; i++) {
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     int ih = ih0[i] + er[e], iw = iw0[i] + et[e];
-                    bool ok = kok[e] && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                    stage_g[i][e] = ok ? p.x[pixoff[i] + off[e]] : (uint16_t)0;
+                    bool ok = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                    unsigned o = ok ? pixbyte[i] + off[e] : kOutOfRange;
+                    stage_g[i][e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rx, (int)o, 0, 0);
                 }
             }
         } else {
-            const int cb = ci * 32 + unit * 4;          // first of this thread's 4 channels
-            const bool cok = cb < p.Cin;
+            const int soff = ci * 64;                   // 32 channels per chunk
 #pragma unroll
-            for (int i = 0; i < ITEMS; i++) {
+            for (int i = 0; i < ITEMS; i++)
 #pragma unroll
-                for (int tap = 0; tap < TAPS; tap++) {
-                    const int r = tap / KW, t = tap % KW;
-                    int ih = ih0[i] + r, iw = iw0[i] + t;
-                    bool ok = cok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                    uint2 v = make_uint2(0, 0);
-                    if (ok) v = *reinterpret_cast<const uint2 *>(p.x + (pixoff[i] + (r * p.W + t) * p.Cin + cb));
-                    stage_t[i][tap] = v;
-                }
-            }
+                for (int tap = 0; tap < TAPS; tap++)
+                    stage_t[i][tap] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)tapoff[i][tap], soff, 0);
         }
     };
     auto stage_store = [&](uint16_t *Bs) {
@@ -225,54 +265,55 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
         for (int i = 0; i < ITEMS; i++) {
             int pr = tid / UNITS + i * (NT / UNITS);
             if constexpr (MODE == MODE_VEC) {
-                *reinterpret_cast<uint4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
+                *reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
             } else if constexpr (MODE == MODE_GATHER) {
                 uint2 v = make_uint2((uint32_t)stage_g[i][0] | ((uint32_t)stage_g[i][1] << 16),
                                      (uint32_t)stage_g[i][2] | ((uint32_t)stage_g[i][3] << 16));
                 *reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * 4) = v;
             } else {
-                // [tap][4 channels] -> [channel][tap]: output element h = c*TAPS + tap, two per dword
-                uint32_t o[2 * TAPS];
+                // [tap][8 channels] -> [channel][tap]: output element h = c*TAPS + tap, two per dword
+                uint32_t o[4 * TAPS];
 #pragma unroll
-                for (int d = 0; d < 2 * TAPS; d++) {
+                for (int d = 0; d < 4 * TAPS; d++) {
                     const int ha = 2 * d, hb = 2 * d + 1;
-                    const int ca = ha / TAPS, ta = ha % TAPS, cbn = hb / TAPS, tb = hb % TAPS;
-                    uint32_t sa = (ca < 2) ? stage_t[i][ta].x : stage_t[i][ta].y;
-                    uint32_t sb = (cbn < 2) ? stage_t[i][tb].x : stage_t[i][tb].y;
+                    const int ca = ha / TAPS, ta = ha % TAPS, cb = hb / TAPS, tb = hb % TAPS;
+                    uint32_t sa = stage_t[i][ta][ca >> 1];
+                    uint32_t sb = stage_t[i][tb][cb >> 1];
                     const uint32_t sel = (uint32_t)(2 * (ca & 1)) | ((uint32_t)(2 * (ca & 1) + 1) << 8) |
-                                         ((uint32_t)(4 + 2 * (cbn & 1)) << 16) | ((uint32_t)(5 + 2 * (cbn & 1)) << 24);
+                                         ((uint32_t)(4 + 2 * (cb & 1)) << 16) | ((uint32_t)(5 + 2 * (cb & 1)) << 24);
                     o[d] = __builtin_amdgcn_perm(sb, sa, sel);
                 }
-                uint2 *dst = reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * (4 * TAPS));
+                u32x4 *dst = reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * (8 * TAPS));
 #pragma unroll
-                for (int d = 0; d < TAPS; d++) dst[d] = make_uint2(o[2 * d], o[2 * d + 1]);
+                for (int d = 0; d < TAPS; d++) {
+                    u32x4 w = {o[4 * d], o[4 * d + 1], o[4 * d + 2], o[4 * d + 3]};
+                    dst[d] = w;
+                }
             }
         }
     };
 
     // ------------------------------------------------------------------ weight fragments
-    const int mt0 = (m0 >> 5) + wm * TM;
-    auto load_a = [&](AStep<SPARSE, TM> &a, int ks) {
+    // Row tiles past the last one are clamped to it (their rows are never stored); reduction steps
+    // past the last one are clamped too: they only ever meet all-zero activations.
+    unsigned a_voff[TM], m_voff[TM];
+#pragma unroll
+    for (int tm = 0; tm < TM; tm++) {
+        int mt = min((m0 >> 5) + wm * TM + tm, p.Mt - 1);
+        a_voff[tm] = (unsigned)((mt * p.Ks * (SPARSE ? 1 : 2)) * 64 + lane) * 16u;
+        m_voff[tm] = (unsigned)(mt * p.Kp * 64 + lane) * 4u;
+    }
+    auto load_a = [&](AStep<SPARSE, TM> &a, int ks_raw) {
+        const int ks = min(ks_raw, p.Ks - 1);
 #pragma unroll
         for (int tm = 0; tm < TM; tm++) {
-            int mt = mt0 + tm;
-            bool ok = ks < p.Ks && mt < p.Mt;
             if constexpr (SPARSE) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                uint32_t w = 0x44444444u;
-                if (ok) {
-                    v = *reinterpret_cast<const uint4 *>(p.a_vals + (((size_t)mt * p.Ks + ks) * 64 + lane) * 16);
-                    w = p.a_meta[((size_t)mt * p.Kp + (ks >> 1)) * 64 + lane];
-                }
-                a.v[0][tm] = v;
+                a.v[0][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 1024, 0);
+                uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rm, (int)m_voff[tm], (ks >> 1) * 256, 0);
                 a.idx[tm] = (ks & 1) ? (w >> 16) : w;    // the instruction reads index bits [15:0]
             } else {
-#pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (ok) v = *reinterpret_cast<const uint4 *>(p.a_vals + ((((size_t)mt * p.Ks + ks) * 2 + h) * 64 + lane) * 16);
-                    a.v[h][tm] = v;
-                }
+                a.v[0][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 2048, 0);
+                a.v[1][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 2048 + 1024, 0);
             }
         }
     };
@@ -305,8 +346,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 #pragma unroll
             for (int tn = 0; tn < TN; tn++) {
                 const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
-                b[tn].lo = *reinterpret_cast<const uint4 *>(src);
-                b[tn].hi = *reinterpret_cast<const uint4 *>(src + 8);
+                b[tn].lo = *reinterpret_cast<const u32x4 *>(src);
+                b[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
             }
             const AStep<SPARSE, TM> &as = a[s % RING];
 #pragma unroll
@@ -314,7 +355,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
                     if constexpr (SPARSE) {
-                        acc[tm][tn] = mma_sparse<DT, 0>(as.v[0][tm], b[tn], acc[tm][tn], as.idx[tm]);
+                        acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[tn], acc[tm][tn], as.idx[tm]);
                     } else {
                         acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[tn].lo, acc[tm][tn]);
                         acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[tn].hi, acc[tm][tn]);
@@ -325,37 +366,53 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
         __syncthreads();
     }
 
-    // ------------------------------------------------------------------ epilogue: bias, activation, one rounding, NHWC store
-    const bool vec_ok = (p.Cout & 3) == 0;
+    // ------------------------------------------------------------------ epilogue
+    // bias + activation in fp32, one rounding to the 16-bit type, then through LDS so that every
+    // pixel's run of BM output channels leaves as 16-byte, fully coalesced NHWC stores.
+    constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
+    uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier
 #pragma unroll
-    for (int tn = 0; tn < TN; tn++) {
-        int pg = n0 + (wn * TN + tn) * 32 + (lane & 31);
-        if (pg >= p.P) continue;
+    for (int tm = 0; tm < TM; tm++) {
 #pragma unroll
-        for (int tm = 0; tm < TM; tm++) {
+        for (int q = 0; q < 4; q++) {
+            const int ol = (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);    // first of 4 consecutive output channels (tile-local)
+            float bv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (p.bias != nullptr) {
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                int o = m0 + (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);
-                if (o >= p.Cout) continue;
+                for (int e = 0; e < 4; e++)
+                    if (m0 + ol + e < p.Cout) bv[e] = p.bias[m0 + ol + e];
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; tn++) {
                 float r[4];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    float v = acc[tm][tn][4 * q + e];
-                    if (p.bias != nullptr && o + e < p.Cout) v += p.bias[o + e];
+                    float v = acc[tm][tn][4 * q + e] + bv[e];
                     if (p.act == SS_ACT_RELU) v = v > 0.f ? v : (v != v ? v : 0.f);
                     r[e] = v;
                 }
-                uint16_t *dst = p.y + (size_t)pg * p.Cout + o;
-                if (vec_ok) {
-                    *reinterpret_cast<uint2 *>(dst) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
-                } else {
-                    uint32_t lo = cvt_pack2<DT>(r[0], r[1]), hi = cvt_pack2<DT>(r[2], r[3]);
-                    dst[0] = (uint16_t)lo;
-                    if (o + 1 < p.Cout) dst[1] = (uint16_t)(lo >> 16);
-                    if (o + 2 < p.Cout) dst[2] = (uint16_t)hi;
-                    if (o + 3 < p.Cout) dst[3] = (uint16_t)(hi >> 16);
-                }
+                const int pl = (wn * TN + tn) * 32 + (lane & 31);
+                *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
             }
+        }
+    }
+    __syncthreads();
+    constexpr int RUNS = BM / 8;                  // 16-byte runs per pixel row
+    const bool vec_ok = (p.Cout & 7) == 0;
+    for (int it = tid; it < BN * RUNS; it += NT) {
+        const int pl = it / RUNS, run = it % RUNS;
+        const int pg = n0 + pl, o = m0 + run * 8;
+        if (pg >= p.P || o >= p.Cout) continue;
+        const uint2 lo = *reinterpret_cast<const uint2 *>(Cs + pl * CROW + run * 8);
+        const uint2 hi = *reinterpret_cast<const uint2 *>(Cs + pl * CROW + run * 8 + 4);
+        uint16_t *dst = p.y + (size_t)pg * p.Cout + o;
+        if (vec_ok) {
+            *reinterpret_cast<uint4 *>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        } else {
+            const uint32_t w[4] = {lo.x, lo.y, hi.x, hi.y};
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                if (o + e < p.Cout) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
         }
     }
 }
@@ -367,9 +424,7 @@ template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MOD
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr int KSTEPS = (MODE == MODE_TAPS) ? KH * KW : 2;
-    constexpr int ROW = KSTEPS * 32 + 8;
-    constexpr size_t smem = (size_t)2 * BN * ROW * sizeof(uint16_t);
+    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW>();
     static_assert(smem <= 160 * 1024, "LDS tile too large");
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
@@ -390,18 +445,24 @@ static int launch(const ConvParams &p0, hipStream_t s)
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
 }
 
+static inline long long n_blocks(const ConvParams &p, int bm, int bn)
+{
+    return (long long)((p.Cout + bm - 1) / bm) * (((long long)p.P + bn - 1) / bn);
+}
+
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
-    // Enough workgroups to cover the 256 compute units decides the tile size.
-    long long big = (long long)((p.Cout + 127) / 128) * ((p.P + 127) / 128);
+    // The largest tile that still yields enough workgroups for the 256 compute units.
     if constexpr (MODE == MODE_TAPS && KH * KW > 4) {
-        // a 128-pixel tile of the 3x3 unfold does not fit LDS twice: 128 x 64 is the large shape
-        if (p.Cout > 64 && big >= 128) return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
+        // 64-pixel tiles: the unfolded 3x3 chunk (64 x 288) is double-buffered in 74 KB of LDS
+        if (p.Cout > 128 && n_blocks(p, 256, 64) >= 200) return launch<DT, SPARSE, 2, 2, 4, 1, MODE, KH, KW>(p, s);
+        if (p.Cout > 64 && n_blocks(p, 128, 64) >= 128) return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
+        return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
     } else {
-        if (p.Cout > 64 && big >= 256) return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
+        if (p.Cout > 64 && n_blocks(p, 128, 128) >= 200) return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
+        return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
     }
-    return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
 }
 
 template <int DT, bool SPARSE>
@@ -410,7 +471,7 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
     const int taps = desc->kh * desc->kw;
     // channels contiguous inside every aligned run of 8 reduction indices?
     if ((desc->cin % 8 == 0) && (desc->korder == SS_K_RSC || taps == 1)) return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
-    if (desc->korder == SS_K_CRS && desc->cin % 4 == 0) {
+    if (desc->korder == SS_K_CRS && desc->cin % 32 == 0) {
         if (desc->kh == 3 && desc->kw == 3) return pick_tile<DT, SPARSE, MODE_TAPS, 3, 3>(p, s);
         if (desc->kh == 2 && desc->kw == 2) return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);
     }
@@ -430,18 +491,20 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     if (N <= 0 || H <= 0 || Wd <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return SS_ERR_INVALID_ARG;
     if (act != SS_ACT_NONE && act != SS_ACT_RELU) return SS_ERR_INVALID_ARG;
     if (H + 2 * ph < desc->kh || Wd + 2 * pw < desc->kw) return SS_ERR_INVALID_ARG;
-    if (!aligned(x, 16) || !aligned(wbuf, 16) || !aligned(y, 8) || (bias && !aligned(bias, 4))) return SS_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(wbuf, 16) || !aligned(y, 16) || (bias && !aligned(bias, 4))) return SS_ERR_INVALID_ARG;
     int Ho = (H + 2 * ph - desc->kh) / sh + 1;
     int Wo = (Wd + 2 * pw - desc->kw) / sw + 1;
     if (Ho <= 0 || Wo <= 0) return SS_ERR_INVALID_ARG;
     long long P = (long long)N * Ho * Wo;
-    long long xelems = (long long)N * H * Wd * desc->cin;
+    long long xbytes = (long long)N * H * Wd * desc->cin * 2;
     long long yelems = P * desc->cout;
-    // 32-bit element offsets inside the kernel (with head-room for the padded halo arithmetic)
-    if (xelems >= (1ll << 31) - (1ll << 24) || yelems >= (1ll << 31) || P >= (1ll << 31) - 256) return SS_ERR_UNSUPPORTED;
-    if ((long long)(ph + desc->kh) * Wd * desc->cin >= (1ll << 30)) return SS_ERR_UNSUPPORTED;
+    // 32-bit byte offsets inside the kernel; "out of range" must stay above every real offset
+    if (xbytes >= (1ll << 31) - (1ll << 26) || yelems >= (1ll << 31) || P >= (1ll << 31) - 512) return SS_ERR_UNSUPPORTED;
+    if ((long long)(ph + desc->kh + 1) * (Wd + pw + desc->kw) * desc->cin * 2 >= (1ll << 26)) return SS_ERR_UNSUPPORTED;
 
     TileDims t = tile_dims(desc);
+    size_t wbytes = SPARSE ? packed_size(t) : dense_size(t);
+    if (wbytes >= (1ull << 31)) return SS_ERR_UNSUPPORTED;
     ConvParams p;
     p.x = static_cast<const uint16_t *>(x);
     p.a_vals = static_cast<const uint8_t *>(wbuf) + kHeaderBytes;
@@ -452,6 +515,9 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.Ho = Ho; p.Wo = Wo; p.P = (int)P;
     p.K = t.K; p.Ks = t.Ks; p.Kp = t.Kp; p.Mt = t.Mt; p.act = act; p.korder = desc->korder;
     p.tiles_m = 0;
+    p.x_bytes = (unsigned)xbytes;
+    p.a_bytes = (unsigned)((size_t)t.Mt * t.Ks * (SPARSE ? 1024 : 2048));
+    p.meta_bytes = SPARSE ? (unsigned)((size_t)t.Mt * t.Kp * 256) : 4u;
     hipStream_t s = static_cast<hipStream_t>(stream);
     return desc->dtype == SS_F16 ? pick_mode<SS_F16, SPARSE>(desc, p, s) : pick_mode<SS_BF16, SPARSE>(desc, p, s);
 }
