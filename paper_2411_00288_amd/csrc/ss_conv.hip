@@ -19,6 +19,7 @@
 // the zero padding, past the last pixel or past the reduction length presents an offset beyond the
 // buffer's size and the hardware returns 0 -- no branches, no selects.
 #include "ss_internal.h"
+#include <cstdlib>
 
 namespace ss {
 
@@ -83,6 +84,9 @@ __device__ __forceinline__ uint32_t cvt_pack2(float a, float b)
 //   MODE_VEC    channels are contiguous inside every aligned run of 8 reduction indices (1x1
 //               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads,
 //               chunks of 64 reduction indices.
+//   MODE_PW     MODE_VEC specialised for 1x1 kernels: a pixel's offset is fixed for the whole
+//               reduction and the chunk's channel offset travels in the load's scalar offset.
+//               Chunks of 128 reduction indices (MODE_PW) or 64 (MODE_PW2, for very short reductions).
 //   MODE_GATHER any flattening / shape: one 16-bit load per element (slow, general fallback).
 //   MODE_TAPS   the paper's flattening (channel slowest) with a KH x KW kernel and cin % 32 == 0:
 //               a 2:4 block then holds 4 consecutive (channel, tap) pairs, i.e. activations of
@@ -90,7 +94,7 @@ __device__ __forceinline__ uint32_t cvt_pack2(float a, float b)
 //               KH*KW taps as 16-byte channel vectors and transposes them in registers to
 //               channel-major order before the LDS write, so the MFMA side still reads 16-byte
 //               vectors.  A chunk is 32 channels = KH*KW reduction steps.
-enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2 };
+enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2, MODE_PW = 3, MODE_PW2 = 4 };
 
 // Weight fragments of one 32-wide reduction step for the TM row tiles of a wave.
 template <bool SPARSE, int TM>
@@ -102,15 +106,31 @@ struct AStep {
 template <int MODE, int KH, int KW>
 struct ChunkShape {
     static constexpr int TAPS = KH * KW;
-    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : 2;   // 32-wide reduction steps per LDS chunk
+    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per LDS chunk
     static constexpr int BK = KSTEPS * 32;
     static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
+    // LDS copies of the chunk: the large unfolded 3x3 chunk is kept once (more workgroups per compute
+    // unit hide the store phase); the small chunks are double-buffered.
+    static constexpr int NBUF = (MODE == MODE_TAPS && TAPS > 4) ? 1 : 2;
 };
+
+constexpr int ring_size(int ksteps, int regs_per_step)
+{
+    int depth = 24 / regs_per_step + 1;
+    if (depth > 12) depth = 12;
+    if (depth < 2) depth = 2;
+    int best = 1;
+    for (int r = 2; r <= depth; r++)
+        if (ksteps % r == 0 || r % ksteps == 0) best = r;
+    if (best >= 2) return best;
+    for (int r = depth + 1;; r++)                    // nothing that shallow nests with the chunk: take the next that does
+        if (ksteps % r == 0 || r % ksteps == 0) return r;
+}
 
 template <int BM, int BN, int MODE, int KH, int KW>
 constexpr size_t smem_bytes()
 {
-    size_t stage = (size_t)2 * BN * ChunkShape<MODE, KH, KW>::ROW * 2;
+    size_t stage = (size_t)ChunkShape<MODE, KH, KW>::NBUF * BN * ChunkShape<MODE, KH, KW>::ROW * 2;
     size_t epi = (size_t)BN * (BM * 2 + 8);
     return stage > epi ? stage : epi;
 }
@@ -124,14 +144,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int TAPS = CS::TAPS;
     constexpr int KSTEPS = CS::KSTEPS;
-    constexpr int RING = (KSTEPS % 3 == 0) ? 3 : ((KSTEPS % 4 == 0) ? 4 : 2);   // weight prefetch ring, divides KSTEPS
+    // Weight fragments are prefetched RING-1 reduction steps ahead into a register ring, as deep as
+    // about 24 VGPRs allow (deeper rings cost occupancy, which the bandwidth-bound layers need more); RING divides the chunk or is a multiple of it (then the chunk loop is
+    // unrolled RING/KSTEPS times so that every ring slot is a compile-time register).
+    constexpr int RING = ring_size(KSTEPS, TM * (SPARSE ? 5 : 8));
     constexpr int PF = RING - 1;
-    static_assert(KSTEPS % RING == 0, "ring must divide the chunk");
+    constexpr int UNROLL = RING > KSTEPS ? RING / KSTEPS : 1;
+    static_assert(KSTEPS % RING == 0 || RING % KSTEPS == 0, "ring and chunk must nest");
     constexpr int BK = CS::BK;
     constexpr int ROW = CS::ROW;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t *Bs0 = smem;
-    uint16_t *Bs1 = smem + BN * ROW;
+    constexpr int NBUF = CS::NBUF;
+    uint16_t *Bs1 = smem + (NBUF - 1) * BN * ROW;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -150,7 +175,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
-    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : 8);
+    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8));
     constexpr int ITEMS = BN * UNITS / NT;
     static_assert(BN * UNITS % NT == 0 && NT % UNITS == 0 && ITEMS >= 1, "tile/threads mismatch");
     const int unit = tid % UNITS;
@@ -198,7 +223,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
             }
     }
 
-    u32x4 stage_v[MODE == MODE_VEC ? ITEMS : 1];
+    // MODE_PW: per pixel byte offset of this thread's 16-byte run in the first chunk (out of range for pixels
+    // past the end or in the padding)
+    unsigned pwoff[(MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
+    if constexpr (MODE == MODE_PW || MODE == MODE_PW2) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; i++) {
+            bool ok = (unsigned)ih0[i] < (unsigned)p.H && (unsigned)iw0[i] < (unsigned)p.W;
+            pwoff[i] = ok ? pixbyte[i] + (unsigned)(unit * 16) : kOutOfRange;
+        }
+    }
+
+    u32x4 stage_v[(MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
     uint16_t stage_g[MODE == MODE_GATHER ? ITEMS : 1][4];
     u32x4 stage_t[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
@@ -218,6 +254,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
                 vc -= p.Cin;
                 if (++vt == p.kw) { vt = 0; ++vr; }
             }
+        } else if constexpr (MODE == MODE_PW || MODE == MODE_PW2) {
+            const bool kok = ci * BK + unit * 8 < p.K;      // the last chunk may reach past the reduction length
+#pragma unroll
+            for (int i = 0; i < ITEMS; i++)
+                stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(kok ? pwoff[i] : kOutOfRange), ci * (BK * 2), 0);
         } else if constexpr (MODE == MODE_GATHER) {
             unsigned off[4];
             int er[4], et[4];
@@ -264,7 +305,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 #pragma unroll
         for (int i = 0; i < ITEMS; i++) {
             int pr = tid / UNITS + i * (NT / UNITS);
-            if constexpr (MODE == MODE_VEC) {
+            if constexpr (MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) {
                 *reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
             } else if constexpr (MODE == MODE_GATHER) {
                 uint2 v = make_uint2((uint32_t)stage_g[i][0] | ((uint32_t)stage_g[i][1] << 16),
@@ -334,36 +375,49 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
     for (int s = 0; s < PF; s++) load_a(a[s], s);
     stage_store(Bs0);
     __syncthreads();
-    for (int ci = 0; ci < nchunks; ci++) {
-        const uint16_t *cur = (ci & 1) ? Bs1 : Bs0;
-        uint16_t *nxt = (ci & 1) ? Bs0 : Bs1;
-        const bool more = ci + 1 < nchunks;
-        if (more) stage_load(ci + 1);
+    for (int c0 = 0; c0 < nchunks; c0 += UNROLL) {
 #pragma unroll
-        for (int s = 0; s < KSTEPS; s++) {
-            load_a(a[(s + PF) % RING], ci * KSTEPS + s + PF);
-            B32 b[TN];
-#pragma unroll
-            for (int tn = 0; tn < TN; tn++) {
-                const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
-                b[tn].lo = *reinterpret_cast<const u32x4 *>(src);
-                b[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
-            }
-            const AStep<SPARSE, TM> &as = a[s % RING];
-#pragma unroll
-            for (int tm = 0; tm < TM; tm++)
+        for (int u = 0; u < UNROLL; u++) {
+            const int ci = c0 + u;
+            if (ci >= nchunks) break;                       // uniform
+            const uint16_t *cur = (ci & 1) ? Bs1 : Bs0;
+            uint16_t *nxt = (ci & 1) ? Bs0 : Bs1;
+            const bool more = ci + 1 < nchunks;
+            if (more) stage_load(ci + 1);
+            B32 b[2][TN];
+            auto load_b = [&](B32 (&bf)[TN], int s) {
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
-                    if constexpr (SPARSE) {
-                        acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[tn], acc[tm][tn], as.idx[tm]);
-                    } else {
-                        acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[tn].lo, acc[tm][tn]);
-                        acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[tn].hi, acc[tm][tn]);
-                    }
+                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
+                    bf[tn].lo = *reinterpret_cast<const u32x4 *>(src);
+                    bf[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
                 }
+            };
+            load_b(b[0], 0);
+#pragma unroll
+            for (int s = 0; s < KSTEPS; s++) {
+                const int g = u * KSTEPS + s;               // position in the ring (compile time)
+                load_a(a[(g + PF) % RING], ci * KSTEPS + s + PF);
+                if (s + 1 < KSTEPS) load_b(b[(s + 1) & 1], s + 1);     // next step's activations while this step multiplies
+                // (steps past the reduction length multiply clamped weights with all-zero activations:
+                // cheaper than a branch, which would force copies of every accumulator)
+                const AStep<SPARSE, TM> &as = a[g % RING];
+#pragma unroll
+                for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++) {
+                        if constexpr (SPARSE) {
+                            acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s & 1][tn], acc[tm][tn], as.idx[tm]);
+                        } else {
+                            acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[s & 1][tn].lo, acc[tm][tn]);
+                            acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[s & 1][tn].hi, acc[tm][tn]);
+                        }
+                    }
+            }
+            if constexpr (NBUF == 1) __syncthreads();       // everyone is done reading the only copy
+            if (more) stage_store(nxt);
+            __syncthreads();
         }
-        if (more) stage_store(nxt);
-        __syncthreads();
     }
 
     // ------------------------------------------------------------------ epilogue
@@ -450,19 +504,52 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
     return (long long)((p.Cout + bm - 1) / bm) * (((long long)p.P + bn - 1) / bn);
 }
 
+// Tile shapes (WAVES_M x WAVES_N waves, each TM x TN tiles of 32x32):
+//   id 0:  64 x  64 (2x2 waves, 1x1)      id 1: 128 x 128 (2x2, 2x2)     id 2: 256 x  64 (2x2, 4x1)
+//   id 3: 128 x  64 (2x2, 2x1)            id 4: 256 x  64 (4x1, 2x2)     id 5: 128 x  64 (4x1, 1x2)
+//   id 6: 256 x 128 (4x1, 2x4)            id 7: 256 x 128 (2x2, 4x2)     id 8:  64 x 128 (1x4, 2x1)
+template <int DT, bool SPARSE, int MODE, int KH, int KW>
+static int launch_tile(int id, const ConvParams &p, hipStream_t s)
+{
+    constexpr bool wide_ok = !(MODE == MODE_TAPS && KH * KW > 4);   // 128-pixel tiles of the unfolded 3x3 chunk exceed LDS
+    switch (id) {
+        case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
+        case 2: return launch<DT, SPARSE, 2, 2, 4, 1, MODE, KH, KW>(p, s);
+        case 3: return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
+        case 4: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW>(p, s);
+        case 5: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW>(p, s);
+        default: break;
+    }
+    if constexpr (wide_ok) {
+        switch (id) {
+            case 1: return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
+            case 6: return launch<DT, SPARSE, 4, 1, 2, 4, MODE, KH, KW>(p, s);
+            case 7: return launch<DT, SPARSE, 2, 2, 4, 2, MODE, KH, KW>(p, s);
+            case 8: return launch<DT, SPARSE, 1, 4, 2, 1, MODE, KH, KW>(p, s);
+            default: break;
+        }
+    }
+    return SS_ERR_INVALID_ARG;
+}
+
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
-    // The largest tile that still yields enough workgroups for the 256 compute units.
-    if constexpr (MODE == MODE_TAPS && KH * KW > 4) {
-        // 64-pixel tiles: the unfolded 3x3 chunk (64 x 288) is double-buffered in 74 KB of LDS
-        if (p.Cout > 128 && n_blocks(p, 256, 64) >= 200) return launch<DT, SPARSE, 2, 2, 4, 1, MODE, KH, KW>(p, s);
-        if (p.Cout > 64 && n_blocks(p, 128, 64) >= 128) return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
-        return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
-    } else {
-        if (p.Cout > 64 && n_blocks(p, 128, 128) >= 200) return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
-        return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
+    constexpr bool wide_ok = !(MODE == MODE_TAPS && KH * KW > 4);
+    const char *env = getenv("SS_TILE");               // tuning aid: force a tile shape by id
+    const int forced = env ? atoi(env) : -1;
+    if (forced >= 0) {
+        int st = launch_tile<DT, SPARSE, MODE, KH, KW>(forced, p, s);
+        if (st != SS_ERR_INVALID_ARG) return st;
     }
+    // Measured on MI355X: layouts with all four waves along the output channels (no weight tile is
+    // fetched twice within a workgroup) win almost everywhere; the tile grows with the number of
+    // workgroups available to fill the 256 compute units.
+    if (p.Cout <= 64) return launch_tile<DT, SPARSE, MODE, KH, KW>(0, p, s);
+    if (!wide_ok || p.Cout <= 128) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
+    if (n_blocks(p, 256, 128) >= 384 && p.K <= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(6, p, s);
+    if (n_blocks(p, 256, 64) >= 384) return launch_tile<DT, SPARSE, MODE, KH, KW>(4, p, s);
+    return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
 }
 
 template <int DT, bool SPARSE>
@@ -470,7 +557,9 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
 {
     const int taps = desc->kh * desc->kw;
     // channels contiguous inside every aligned run of 8 reduction indices?
-    if ((desc->cin % 8 == 0) && (desc->korder == SS_K_RSC || taps == 1)) return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
+    if (desc->cin % 8 == 0 && taps == 1)
+        return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
+    if (desc->cin % 8 == 0 && desc->korder == SS_K_RSC) return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
     if (desc->korder == SS_K_CRS && desc->cin % 32 == 0) {
         if (desc->kh == 3 && desc->kw == 3) return pick_tile<DT, SPARSE, MODE_TAPS, 3, 3>(p, s);
         if (desc->kh == 2 && desc->kw == 2) return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);
