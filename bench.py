@@ -197,6 +197,9 @@ def main():
     ap.add_argument("--table", action="store_true", help="per-layer report for all configurations instead of the JSON line")
     ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
+    ap.add_argument("--profile-run", action="store_true",
+                    help="for rocprofv3: one 64 MiB device copy (calibrates the traffic counters), then 20 sparse and "
+                         "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -218,6 +221,21 @@ def main():
 
     L = wl.CONFIG1
     run = LayerRun(L, torch, ss, wl)
+
+    if args.profile_run:
+        src = torch.ones(32 << 20, dtype=torch.float16, device="cuda")      # 64 MiB read + 64 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        for _ in range(20):
+            run.sparse()
+        torch.cuda.synchronize()
+        for _ in range(20):
+            run.densef()
+        torch.cuda.synchronize()
+        print("profile-run done: 1 copy of 67108864 bytes, 20 sparse, 20 dense launches", flush=True)
+        return
 
     # ---- the timed region: exactly `steps` launches of the sparse convolution, recorded in one HIP
     # graph (a launch lasts a few microseconds, less than the host needs to issue one), replayed

@@ -132,11 +132,20 @@ constexpr size_t smem_bytes()
 {
     size_t stage = (size_t)ChunkShape<MODE, KH, KW>::NBUF * BN * ChunkShape<MODE, KH, KW>::ROW * 2;
     size_t epi = (size_t)BN * (BM * 2 + 8);
-    return stage > epi ? stage : epi;
+    return (stage > epi ? stage : epi) + (size_t)BM * 4;      // + the tile's bias values (fp32)
+}
+
+// Waves per SIMD the register allocator must leave room for: small wave tiles are latency-bound
+// and profit from 4 resident waves (128 VGPRs each); large ones need the registers.
+constexpr int min_waves_per_simd(int tm, int tn)
+{
+    return tm * tn <= 2 ? 4 : (tm * tn <= 4 ? 2 : 1);
 }
 
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams p)
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64)
+__attribute__((amdgpu_waves_per_eu(min_waves_per_simd(TM, TN))))
+void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW>;
     constexpr int NT = WAVES_M * WAVES_N * 64;
@@ -172,6 +181,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.x), 0, (int)p.x_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a_vals), 0, (int)p.a_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a_meta), 0, (int)p.meta_bytes, kRsrcFlags);
+
+    // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
+    // epilogue does not pay a global-memory round trip.
+    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW>() - (size_t)BM * 4));
+    float bias_r[(BM + NT - 1) / NT];
+#pragma unroll
+    for (int j = 0; j < (BM + NT - 1) / NT; j++) {
+        const int o = m0 + tid + j * NT;
+        bias_r[j] = (p.bias != nullptr && tid + j * NT < BM && o < p.Cout) ? p.bias[o] : 0.f;
+    }
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
@@ -374,6 +393,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 #pragma unroll
     for (int s = 0; s < PF; s++) load_a(a[s], s);
     stage_store(Bs0);
+#pragma unroll
+    for (int j = 0; j < (BM + NT - 1) / NT; j++)
+        if (tid + j * NT < BM) bias_s[tid + j * NT] = bias_r[j];
     __syncthreads();
     for (int c0 = 0; c0 < nchunks; c0 += UNROLL) {
 #pragma unroll
@@ -430,12 +452,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void conv_kernel(ConvParams 
 #pragma unroll
         for (int q = 0; q < 4; q++) {
             const int ol = (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);    // first of 4 consecutive output channels (tile-local)
-            float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (p.bias != nullptr) {
-#pragma unroll
-                for (int e = 0; e < 4; e++)
-                    if (m0 + ol + e < p.Cout) bv[e] = p.bias[m0 + ol + e];
-            }
+            const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
+            const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
 #pragma unroll
             for (int tn = 0; tn < TN; tn++) {
                 float r[4];
@@ -508,26 +526,26 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
 //   id 0:  64 x  64 (2x2 waves, 1x1)      id 1: 128 x 128 (2x2, 2x2)     id 2: 256 x  64 (2x2, 4x1)
 //   id 3: 128 x  64 (2x2, 2x1)            id 4: 256 x  64 (4x1, 2x2)     id 5: 128 x  64 (4x1, 1x2)
 //   id 6: 256 x 128 (4x1, 2x4)            id 7: 256 x 128 (2x2, 4x2)     id 8:  64 x 128 (1x4, 2x1)
+//   id 9: 256 x 128 (8x1, 1x4)            id 10: 256 x 128 (4x2, 2x2)    id 11: 128 x 128 (4x1, 1x4)
+//   id 12: 128 x 128 (4x2, 1x2)
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int launch_tile(int id, const ConvParams &p, hipStream_t s)
 {
-    constexpr bool wide_ok = !(MODE == MODE_TAPS && KH * KW > 4);   // 128-pixel tiles of the unfolded 3x3 chunk exceed LDS
     switch (id) {
         case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
+        case 1: return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
         case 2: return launch<DT, SPARSE, 2, 2, 4, 1, MODE, KH, KW>(p, s);
         case 3: return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
         case 4: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW>(p, s);
         case 5: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW>(p, s);
+        case 6: return launch<DT, SPARSE, 4, 1, 2, 4, MODE, KH, KW>(p, s);
+        case 7: return launch<DT, SPARSE, 2, 2, 4, 2, MODE, KH, KW>(p, s);
+        case 8: return launch<DT, SPARSE, 1, 4, 2, 1, MODE, KH, KW>(p, s);
+        case 9: return launch<DT, SPARSE, 8, 1, 1, 4, MODE, KH, KW>(p, s);
+        case 10: return launch<DT, SPARSE, 4, 2, 2, 2, MODE, KH, KW>(p, s);
+        case 11: return launch<DT, SPARSE, 4, 1, 1, 4, MODE, KH, KW>(p, s);
+        case 12: return launch<DT, SPARSE, 4, 2, 1, 2, MODE, KH, KW>(p, s);
         default: break;
-    }
-    if constexpr (wide_ok) {
-        switch (id) {
-            case 1: return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
-            case 6: return launch<DT, SPARSE, 4, 1, 2, 4, MODE, KH, KW>(p, s);
-            case 7: return launch<DT, SPARSE, 2, 2, 4, 2, MODE, KH, KW>(p, s);
-            case 8: return launch<DT, SPARSE, 1, 4, 2, 1, MODE, KH, KW>(p, s);
-            default: break;
-        }
     }
     return SS_ERR_INVALID_ARG;
 }
@@ -535,7 +553,7 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
-    constexpr bool wide_ok = !(MODE == MODE_TAPS && KH * KW > 4);
+    constexpr bool wide_ok = !(MODE == MODE_TAPS && KH * KW > 4);   // 3x3: the unfolded chunk is large, prefer 64-pixel tiles
     const char *env = getenv("SS_TILE");               // tuning aid: force a tile shape by id
     const int forced = env ? atoi(env) : -1;
     if (forced >= 0) {
@@ -547,7 +565,7 @@ static int pick_tile(const ConvParams &p, hipStream_t s)
     // workgroups available to fill the 256 compute units.
     if (p.Cout <= 64) return launch_tile<DT, SPARSE, MODE, KH, KW>(0, p, s);
     if (!wide_ok || p.Cout <= 128) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
-    if (n_blocks(p, 256, 128) >= 384 && p.K <= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(6, p, s);
+    if (n_blocks(p, 256, 128) >= 384 && p.K > 64 && p.K <= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(6, p, s);
     if (n_blocks(p, 256, 64) >= 384) return launch_tile<DT, SPARSE, MODE, KH, KW>(4, p, s);
     return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
 }
