@@ -198,7 +198,7 @@ def main():
     ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
     ap.add_argument("--profile-run", action="store_true",
-                    help="for rocprofv3: one 64 MiB device copy (calibrates the traffic counters), then 20 sparse and "
+                    help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
                          "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
@@ -223,18 +223,19 @@ def main():
     run = LayerRun(L, torch, ss, wl)
 
     if args.profile_run:
-        src = torch.ones(32 << 20, dtype=torch.float16, device="cuda")      # 64 MiB read + 64 MiB written
-        dst = torch.empty_like(src)
+        src = torch.ones(256 << 20, dtype=torch.float16, device="cuda")     # 512 MiB read + 512 MiB written:
+        dst = torch.empty_like(src)                                        # larger than every cache level
         torch.cuda.synchronize()
-        dst.copy_(src)
+        torch.mul(src, 1.0, out=dst)                                       # a plain streaming copy kernel
         torch.cuda.synchronize()
+        del src, dst
         for _ in range(20):
             run.sparse()
         torch.cuda.synchronize()
         for _ in range(20):
             run.densef()
         torch.cuda.synchronize()
-        print("profile-run done: 1 copy of 67108864 bytes, 20 sparse, 20 dense launches", flush=True)
+        print("profile-run done: 1 streaming copy of 536870912 bytes, 20 sparse, 20 dense launches", flush=True)
         return
 
     # ---- the timed region: exactly `steps` launches of the sparse convolution, recorded in one HIP

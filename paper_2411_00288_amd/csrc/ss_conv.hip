@@ -137,14 +137,14 @@ constexpr size_t smem_bytes()
 
 // Waves per SIMD the register allocator must leave room for: small wave tiles are latency-bound
 // and profit from 4 resident waves (128 VGPRs each); large ones need the registers.
-constexpr int min_waves_per_simd(int tm, int tn)
+constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 {
-    return tm * tn <= 2 ? 4 : (tm * tn <= 4 ? 2 : 1);
+    return tm * tn <= 2 ? (big_stage ? 3 : 4) : (tm * tn <= 4 ? 2 : 1);   // the 3x3 transpose needs ~134 VGPRs: 4 waves would spill
 }
 
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64)
-__attribute__((amdgpu_waves_per_eu(min_waves_per_simd(TM, TN))))
+__attribute__((amdgpu_waves_per_eu(min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW>;
@@ -172,8 +172,13 @@ void conv_kernel(ConvParams p)
     const int wave = tid >> 6;
     const int wm = wave % WAVES_M;
     const int wn = wave / WAVES_M;
-    const int tile_m = blockIdx.x % p.tiles_m;
-    const int tile_n = blockIdx.x / p.tiles_m;
+    // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Renumber them so
+    // that an XCD works on a contiguous run of tiles: both row tiles of a pixel tile, and pixel tiles
+    // that share halo rows, then hit the same L2.
+    const int nb = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int lid = xcd * (nb >> 3) + min(xcd, nb & 7) + slot;
+    const int tile_m = lid % p.tiles_m;
+    const int tile_n = lid / p.tiles_m;
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
     const int HoWo = p.Ho * p.Wo;
