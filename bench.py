@@ -26,6 +26,9 @@ sys.path.insert(0, str(ROOT))
 SPARSE_PEAK_TFLOPS = 5000.0   # 2:4-sparse fp16/bf16 MFMA, dense-equivalent = 2 x the 2.5 PFLOP/s dense peak
 DENSE_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the sparse kernel on configs[1], from the rocprofv3 counter runs summarised in
+# profiles/conv_kernel_cfg1_hbm_traffic.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (factors from a streaming copy).
+CFG1_TRAFFIC_BYTES = int((2.0 * 4302.5 + 1.0 * 3136.0) * 1024)
 
 
 def _to_dev(bits, dtype, torch, ss):
@@ -200,6 +203,8 @@ def main():
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
                          "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n512", "cfg2"],
+                    help="with --profile-run: which layer to launch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -220,7 +225,9 @@ def main():
         return
 
     L = wl.CONFIG1
-    run = LayerRun(L, torch, ss, wl)
+    if args.profile_run:
+        L = {"cfg1": wl.CONFIG1, "cfg1_n512": wl.with_batch(wl.CONFIG1, 512), "cfg2": wl.CONFIG2}[args.workload]
+    run = LayerRun(L, torch, ss, wl, values=not args.profile_run)
 
     if args.profile_run:
         src = torch.ones(256 << 20, dtype=torch.float16, device="cuda")     # 512 MiB read + 512 MiB written:
@@ -235,7 +242,7 @@ def main():
         for _ in range(20):
             run.densef()
         torch.cuda.synchronize()
-        print("profile-run done: 1 streaming copy of 536870912 bytes, 20 sparse, 20 dense launches", flush=True)
+        print(f"profile-run done ({L.name}): 1 streaming copy of 536870912 bytes, 20 sparse, 20 dense launches", flush=True)
         return
 
     # ---- the timed region: exactly `steps` launches of the sparse convolution, recorded in one HIP
@@ -271,7 +278,8 @@ def main():
                          "frac_sparse_peak": Lbig.dense_equiv_flop / tb_s / 1e9 / SPARSE_PEAK_TFLOPS},
         "compress_us": tc * 1e3, "eager_launch_us": eager_ms * 1e3,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": CFG1_TRAFFIC_BYTES,
+                     "traffic_unit": "bytes per launch (algorithmic: %d)" % L.algorithmic_bytes(True),
                      "kernel": "ss::conv_kernel (sparse, fp16)", "flop_per_launch": L.dense_equiv_flop,
                      "kernel_us": kern_ms * 1e3},
     }
