@@ -114,9 +114,9 @@ struct ChunkShape {
     static constexpr int NBUF = (MODE == MODE_TAPS && TAPS > 4) ? 1 : 2;
 };
 
-constexpr int ring_size(int ksteps, int regs_per_step)
+constexpr int ring_size(int ksteps, int regs_per_step, int budget)
 {
-    int depth = 24 / regs_per_step + 1;
+    int depth = budget / regs_per_step + 1;
     if (depth > 12) depth = 12;
     if (depth < 2) depth = 2;
     int best = 1;
@@ -142,9 +142,12 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
     return tm * tn <= 2 ? (big_stage ? 3 : 4) : (tm * tn <= 4 ? 2 : 1);   // the 3x3 transpose needs ~134 VGPRs: 4 waves would spill
 }
 
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
+// DEEP: for grids of at most about one workgroup per compute unit, where no other wave hides
+// latency: weight fragments are prefetched 8+ steps ahead and activation fragments 3 steps ahead
+// (instead of 1), at the price of registers, i.e. of the occupancy such a grid cannot use anyway.
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64)
-__attribute__((amdgpu_waves_per_eu(min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
+__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW>;
@@ -154,9 +157,10 @@ void conv_kernel(ConvParams p)
     constexpr int TAPS = CS::TAPS;
     constexpr int KSTEPS = CS::KSTEPS;
     // Weight fragments are prefetched RING-1 reduction steps ahead into a register ring, as deep as
-    // about 24 VGPRs allow (deeper rings cost occupancy, which the bandwidth-bound layers need more); RING divides the chunk or is a multiple of it (then the chunk loop is
+    // about 24 (48 when DEEP) VGPRs allow (deeper rings cost occupancy, which the bandwidth-bound layers need more); RING divides the chunk or is a multiple of it (then the chunk loop is
     // unrolled RING/KSTEPS times so that every ring slot is a compile-time register).
-    constexpr int RING = ring_size(KSTEPS, TM * (SPARSE ? 5 : 8));
+    constexpr int RING = ring_size(KSTEPS, TM * (SPARSE ? 5 : 8), DEEP ? 48 : 24);
+    constexpr int BD = DEEP ? 4 : 2;                      // activation-fragment ring depth
     constexpr int PF = RING - 1;
     constexpr int UNROLL = RING > KSTEPS ? RING / KSTEPS : 1;
     static_assert(KSTEPS % RING == 0 || RING % KSTEPS == 0, "ring and chunk must nest");
@@ -200,14 +204,20 @@ void conv_kernel(ConvParams p)
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
     constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8));
-    constexpr int ITEMS = BN * UNITS / NT;
-    static_assert(BN * UNITS % NT == 0 && NT % UNITS == 0 && ITEMS >= 1, "tile/threads mismatch");
+    constexpr int ST = NT < BN * UNITS ? NT : BN * UNITS;     // staging threads (whole waves); the rest only multiply
+    constexpr int ITEMS = BN * UNITS / ST;
+    static_assert(BN * UNITS % ST == 0 && ST % UNITS == 0 && ST % 64 == 0 && ITEMS >= 1, "tile/threads mismatch");
+    const bool stager = (ST == NT) || tid < ST;
+    // Thread -> (pixel row, unit): unit fastest, so consecutive lanes read consecutive 16-byte pieces of one
+    // pixel (coalesced).  (Putting 16 pixel rows of one unit on consecutive lanes makes the transposed LDS
+    // writes conflict-free but quadruples the cache lines per load instruction: measured 30-40 % slower.)
     const int unit = tid % UNITS;
+    const int pr0 = (tid % ST) / UNITS;
     unsigned pixbyte[ITEMS];          // byte offset of x[n, ho*sh-ph, wo*sw-pw, 0] (wraps below 0 for padded pixels)
     int ih0[ITEMS], iw0[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; i++) {
-        int pr = tid / UNITS + i * (NT / UNITS);
+        int pr = pr0 + i * (ST / UNITS);
         int pg = n0 + pr;
         if (pg < p.P) {
             int n = pg / HoWo;
@@ -263,6 +273,7 @@ void conv_kernel(ConvParams p)
     u32x4 stage_t[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
     auto stage_load = [&](int ci) {
+        if (!stager) return;
         if constexpr (MODE == MODE_VEC) {
             const unsigned koff = vk < p.K ? (unsigned)(((vr * p.W + vt) * p.Cin + vc) * 2) : kOutOfRange;
 #pragma unroll
@@ -326,9 +337,10 @@ void conv_kernel(ConvParams p)
         }
     };
     auto stage_store = [&](uint16_t *Bs) {
+        if (!stager) return;
 #pragma unroll
         for (int i = 0; i < ITEMS; i++) {
-            int pr = tid / UNITS + i * (NT / UNITS);
+            int pr = pr0 + i * (ST / UNITS);
             if constexpr (MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) {
                 *reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
             } else if constexpr (MODE == MODE_GATHER) {
@@ -411,7 +423,8 @@ void conv_kernel(ConvParams p)
             uint16_t *nxt = (ci & 1) ? Bs0 : Bs1;
             const bool more = ci + 1 < nchunks;
             if (more) stage_load(ci + 1);
-            B32 b[2][TN];
+            __builtin_amdgcn_sched_barrier(0);
+            B32 b[BD][TN];
             auto load_b = [&](B32 (&bf)[TN], int s) {
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
@@ -420,12 +433,13 @@ void conv_kernel(ConvParams p)
                     bf[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
                 }
             };
-            load_b(b[0], 0);
+#pragma unroll
+            for (int s = 0; s < BD - 1 && s < KSTEPS; s++) load_b(b[s], s);
 #pragma unroll
             for (int s = 0; s < KSTEPS; s++) {
                 const int g = u * KSTEPS + s;               // position in the ring (compile time)
                 load_a(a[(g + PF) % RING], ci * KSTEPS + s + PF);
-                if (s + 1 < KSTEPS) load_b(b[(s + 1) & 1], s + 1);     // next step's activations while this step multiplies
+                if (s + BD - 1 < KSTEPS) load_b(b[(s + BD - 1) % BD], s + BD - 1);   // later steps' activations while this step multiplies
                 // (steps past the reduction length multiply clamped weights with all-zero activations:
                 // cheaper than a branch, which would force copies of every accumulator)
                 const AStep<SPARSE, TM> &as = a[g % RING];
@@ -434,12 +448,25 @@ void conv_kernel(ConvParams p)
 #pragma unroll
                     for (int tn = 0; tn < TN; tn++) {
                         if constexpr (SPARSE) {
-                            acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s & 1][tn], acc[tm][tn], as.idx[tm]);
+                            acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s % BD][tn], acc[tm][tn], as.idx[tm]);
                         } else {
-                            acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[s & 1][tn].lo, acc[tm][tn]);
-                            acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[s & 1][tn].hi, acc[tm][tn]);
+                            acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[s % BD][tn].lo, acc[tm][tn]);
+                            acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[s % BD][tn].hi, acc[tm][tn]);
                         }
                     }
+                // Scheduling: left alone, the compiler sinks every load to just before its first use and the
+                // prefetch distance collapses to zero.  Pin this step's instructions to the step (barriers at both
+                // ends) and interleave the loads for later steps between its matrix instructions.
+                constexpr int NMMA = TM * TN * (SPARSE ? 1 : 2);
+                constexpr int DSR = (2 * TN + NMMA - 1) / NMMA;
+                constexpr int VMR = (TM * 2 + NMMA - 1) / NMMA;
+#pragma unroll
+                for (int i = 0; i < NMMA; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);    // LDS reads
+                    __builtin_amdgcn_sched_group_barrier(0x020, VMR, 0);    // global reads
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (NBUF == 1) __syncthreads();       // everyone is done reading the only copy
             if (more) stage_store(nxt);
@@ -450,6 +477,7 @@ void conv_kernel(ConvParams p)
     // ------------------------------------------------------------------ epilogue
     // bias + activation in fp32, one rounding to the 16-bit type, then through LDS so that every
     // pixel's run of BM output channels leaves as 16-byte, fully coalesced NHWC stores.
+    const float relu_floor = p.act == SS_ACT_RELU ? 0.f : -__builtin_inff();
     constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
     uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier
 #pragma unroll
@@ -465,8 +493,7 @@ void conv_kernel(ConvParams p)
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     float v = acc[tm][tn][4 * q + e] + bv[e];
-                    if (p.act == SS_ACT_RELU) v = v > 0.f ? v : (v != v ? v : 0.f);
-                    r[e] = v;
+                    r[e] = v < relu_floor ? 0.f : v;      // ReLU when relu_floor = 0, identity when -inf; NaN passes through
                 }
                 const int pl = (wn * TN + tn) * 32 + (lane & 31);
                 *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
@@ -497,7 +524,7 @@ void conv_kernel(ConvParams p)
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW>
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false>
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
@@ -508,7 +535,7 @@ static int launch(const ConvParams &p0, hipStream_t s)
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
-    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW>;
+    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP>;
     if (smem > 64 * 1024) {
         static bool attr_set = false;    // once per process: raises this kernel's dynamic-LDS limit
         if (!attr_set) {
@@ -527,29 +554,23 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
     return (long long)((p.Cout + bm - 1) / bm) * (((long long)p.P + bn - 1) / bn);
 }
 
-// Tile shapes (WAVES_M x WAVES_N waves, each TM x TN tiles of 32x32):
-//   id 0:  64 x  64 (2x2 waves, 1x1)      id 1: 128 x 128 (2x2, 2x2)     id 2: 256 x  64 (2x2, 4x1)
-//   id 3: 128 x  64 (2x2, 2x1)            id 4: 256 x  64 (4x1, 2x2)     id 5: 128 x  64 (4x1, 1x2)
-//   id 6: 256 x 128 (4x1, 2x4)            id 7: 256 x 128 (2x2, 4x2)     id 8:  64 x 128 (1x4, 2x1)
-//   id 9: 256 x 128 (8x1, 1x4)            id 10: 256 x 128 (4x2, 2x2)    id 11: 128 x 128 (4x1, 1x4)
-//   id 12: 128 x 128 (4x2, 1x2)
+// Tile shapes (WAVES_M x WAVES_N waves, each TM x TN tiles of 32x32; "deep" = DEEP prefetch):
+//   id 0:  64 x  64 (2x2 waves, 1x1)       id 1: same, deep
+//   id 2: 128 x  64 (4x1 waves, 1x2)       id 3: same, deep
+//   id 4: 256 x  64 (4x1 waves, 2x2)       id 5: same, deep
+// Layouts with all four waves along the output channels fetch no weight tile twice inside a
+// workgroup; 2x2 layouts of the same tile sizes, 8-wave workgroups, 128x128 and 256x128 tiles were
+// measured and lost everywhere, so they are not instantiated.
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int launch_tile(int id, const ConvParams &p, hipStream_t s)
 {
     switch (id) {
-        case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW>(p, s);
-        case 1: return launch<DT, SPARSE, 2, 2, 2, 2, MODE, KH, KW>(p, s);
-        case 2: return launch<DT, SPARSE, 2, 2, 4, 1, MODE, KH, KW>(p, s);
-        case 3: return launch<DT, SPARSE, 2, 2, 2, 1, MODE, KH, KW>(p, s);
-        case 4: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW>(p, s);
-        case 5: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW>(p, s);
-        case 6: return launch<DT, SPARSE, 4, 1, 2, 4, MODE, KH, KW>(p, s);
-        case 7: return launch<DT, SPARSE, 2, 2, 4, 2, MODE, KH, KW>(p, s);
-        case 8: return launch<DT, SPARSE, 1, 4, 2, 1, MODE, KH, KW>(p, s);
-        case 9: return launch<DT, SPARSE, 8, 1, 1, 4, MODE, KH, KW>(p, s);
-        case 10: return launch<DT, SPARSE, 4, 2, 2, 2, MODE, KH, KW>(p, s);
-        case 11: return launch<DT, SPARSE, 4, 1, 1, 4, MODE, KH, KW>(p, s);
-        case 12: return launch<DT, SPARSE, 4, 2, 1, 2, MODE, KH, KW>(p, s);
+        case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, false>(p, s);
+        case 1: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, true>(p, s);
+        case 2: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, false>(p, s);
+        case 3: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true>(p, s);
+        case 4: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, false>(p, s);
+        case 5: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true>(p, s);
         default: break;
     }
     return SS_ERR_INVALID_ARG;
@@ -565,14 +586,16 @@ static int pick_tile(const ConvParams &p, hipStream_t s)
         int st = launch_tile<DT, SPARSE, MODE, KH, KW>(forced, p, s);
         if (st != SS_ERR_INVALID_ARG) return st;
     }
-    // Measured on MI355X: layouts with all four waves along the output channels (no weight tile is
-    // fetched twice within a workgroup) win almost everywhere; the tile grows with the number of
-    // workgroups available to fill the 256 compute units.
-    if (p.Cout <= 64) return launch_tile<DT, SPARSE, MODE, KH, KW>(0, p, s);
-    if (!wide_ok || p.Cout <= 128) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
-    if (n_blocks(p, 256, 128) >= 384 && p.K > 64 && p.K <= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(6, p, s);
-    if (n_blocks(p, 256, 64) >= 384) return launch_tile<DT, SPARSE, MODE, KH, KW>(4, p, s);
-    return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
+    // Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes).  Deep prefetch pays when
+    // few workgroups share a compute unit (small grids) and for the 3x3 transpose path.
+    constexpr bool pointwise = MODE == MODE_PW || MODE == MODE_PW2;
+    if (p.Cout <= 64) {
+        const bool deep = n_blocks(p, 64, 64) <= 1024 || (pointwise && p.K >= 256);
+        return launch_tile<DT, SPARSE, MODE, KH, KW>(deep ? 1 : 0, p, s);
+    }
+    if (!wide_ok) return launch_tile<DT, SPARSE, MODE, KH, KW>(3, p, s);
+    if (p.Cout >= 512 && p.K >= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
+    return launch_tile<DT, SPARSE, MODE, KH, KW>(n_blocks(p, 128, 64) <= 1024 ? 3 : 2, p, s);
 }
 
 template <int DT, bool SPARSE>
