@@ -103,15 +103,16 @@ struct AStep {
     uint32_t idx[TM];
 };
 
-template <int MODE, int KH, int KW>
+template <int MODE, int KH, int KW, bool DEEP>
 struct ChunkShape {
     static constexpr int TAPS = KH * KW;
     static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per LDS chunk
     static constexpr int BK = KSTEPS * 32;
     static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
-    // LDS copies of the chunk: the large unfolded 3x3 chunk is kept once (more workgroups per compute
-    // unit hide the store phase); the small chunks are double-buffered.
-    static constexpr int NBUF = (MODE == MODE_TAPS && TAPS > 4) ? 1 : 2;
+    // LDS copies of the chunk: double-buffered, so that the next chunk is written while this one is
+    // multiplied -- except for the large unfolded 3x3 chunk in the shallow variant, which is kept once
+    // (more workgroups per compute unit then hide the store phase instead).
+    static constexpr int NBUF = (MODE == MODE_TAPS && TAPS > 4 && !DEEP) ? 1 : 2;
 };
 
 constexpr int ring_size(int ksteps, int regs_per_step, int budget)
@@ -127,10 +128,10 @@ constexpr int ring_size(int ksteps, int regs_per_step, int budget)
         if (ksteps % r == 0 || r % ksteps == 0) return r;
 }
 
-template <int BM, int BN, int MODE, int KH, int KW>
+template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
 constexpr size_t smem_bytes()
 {
-    size_t stage = (size_t)ChunkShape<MODE, KH, KW>::NBUF * BN * ChunkShape<MODE, KH, KW>::ROW * 2;
+    size_t stage = (size_t)ChunkShape<MODE, KH, KW, DEEP>::NBUF * BN * ChunkShape<MODE, KH, KW, DEEP>::ROW * 2;
     size_t epi = (size_t)BN * (BM * 2 + 8);
     return (stage > epi ? stage : epi) + (size_t)BM * 4;      // + the tile's bias values (fp32)
 }
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64)
 __attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
 void conv_kernel(ConvParams p)
 {
-    using CS = ChunkShape<MODE, KH, KW>;
+    using CS = ChunkShape<MODE, KH, KW, DEEP>;
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int BM = WAVES_M * TM * 32;
     constexpr int BN = WAVES_N * TN * 32;
@@ -193,7 +194,7 @@ void conv_kernel(ConvParams p)
 
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
-    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW>() - (size_t)BM * 4));
+    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP>() - (size_t)BM * 4));
     float bias_r[(BM + NT - 1) / NT];
 #pragma unroll
     for (int j = 0; j < (BM + NT - 1) / NT; j++) {
@@ -336,39 +337,47 @@ void conv_kernel(ConvParams p)
                     stage_t[i][tap] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)tapoff[i][tap], soff, 0);
         }
     };
-    auto stage_store = [&](uint16_t *Bs) {
+    // Writes slice j of n of the staged chunk to LDS (j, n are compile-time at every call site): a share of the
+    // transposed 16-byte vectors (tap mode) or of the items (other modes).  stage_store = all of it.
+    auto stage_store_slice = [&](uint16_t *Bs, int j, int n) {
         if (!stager) return;
 #pragma unroll
         for (int i = 0; i < ITEMS; i++) {
             int pr = pr0 + i * (ST / UNITS);
-            if constexpr (MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) {
-                *reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
-            } else if constexpr (MODE == MODE_GATHER) {
-                uint2 v = make_uint2((uint32_t)stage_g[i][0] | ((uint32_t)stage_g[i][1] << 16),
-                                     (uint32_t)stage_g[i][2] | ((uint32_t)stage_g[i][3] << 16));
-                *reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * 4) = v;
-            } else {
-                // [tap][8 channels] -> [channel][tap]: output element h = c*TAPS + tap, two per dword
-                uint32_t o[4 * TAPS];
-#pragma unroll
-                for (int d = 0; d < 4 * TAPS; d++) {
-                    const int ha = 2 * d, hb = 2 * d + 1;
-                    const int ca = ha / TAPS, ta = ha % TAPS, cb = hb / TAPS, tb = hb % TAPS;
-                    uint32_t sa = stage_t[i][ta][ca >> 1];
-                    uint32_t sb = stage_t[i][tb][cb >> 1];
-                    const uint32_t sel = (uint32_t)(2 * (ca & 1)) | ((uint32_t)(2 * (ca & 1) + 1) << 8) |
-                                         ((uint32_t)(4 + 2 * (cb & 1)) << 16) | ((uint32_t)(5 + 2 * (cb & 1)) << 24);
-                    o[d] = __builtin_amdgcn_perm(sb, sa, sel);
-                }
+            if constexpr (MODE == MODE_TAPS) {
+                // [tap][8 channels] -> [channel][tap]: output element h = c*TAPS + tap, two per dword, four dwords per vector
                 u32x4 *dst = reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * (8 * TAPS));
 #pragma unroll
-                for (int d = 0; d < TAPS; d++) {
-                    u32x4 w = {o[4 * d], o[4 * d + 1], o[4 * d + 2], o[4 * d + 3]};
-                    dst[d] = w;
+                for (int v = 0; v < TAPS; v++) {
+                    if (v < j * TAPS / n || v >= (j + 1) * TAPS / n) continue;
+                    uint32_t o[4];
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const int d = 4 * v + q;
+                        const int ha = 2 * d, hb = 2 * d + 1;
+                        const int ca = ha / TAPS, ta = ha % TAPS, cb = hb / TAPS, tb = hb % TAPS;
+                        uint32_t sa = stage_t[i][ta][ca >> 1];
+                        uint32_t sb = stage_t[i][tb][cb >> 1];
+                        const uint32_t sel = (uint32_t)(2 * (ca & 1)) | ((uint32_t)(2 * (ca & 1) + 1) << 8) |
+                                             ((uint32_t)(4 + 2 * (cb & 1)) << 16) | ((uint32_t)(5 + 2 * (cb & 1)) << 24);
+                        o[q] = __builtin_amdgcn_perm(sb, sa, sel);
+                    }
+                    u32x4 w = {o[0], o[1], o[2], o[3]};
+                    dst[v] = w;
+                }
+            } else {
+                if (i < j * ITEMS / n || i >= (j + 1) * ITEMS / n) continue;
+                if constexpr (MODE == MODE_GATHER) {
+                    uint2 v = make_uint2((uint32_t)stage_g[i][0] | ((uint32_t)stage_g[i][1] << 16),
+                                         (uint32_t)stage_g[i][2] | ((uint32_t)stage_g[i][3] << 16));
+                    *reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * 4) = v;
+                } else {
+                    *reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * 8) = stage_v[i];
                 }
             }
         }
     };
+    auto stage_store = [&](uint16_t *Bs) { stage_store_slice(Bs, 0, 1); };
 
     // ------------------------------------------------------------------ weight fragments
     // Row tiles past the last one are clamped to it (their rows are never stored); reduction steps
@@ -440,6 +449,10 @@ void conv_kernel(ConvParams p)
                 const int g = u * KSTEPS + s;               // position in the ring (compile time)
                 load_a(a[(g + PF) % RING], ci * KSTEPS + s + PF);
                 if (s + BD - 1 < KSTEPS) load_b(b[(s + BD - 1) % BD], s + BD - 1);   // later steps' activations while this step multiplies
+                if constexpr (NBUF == 2) {          // the next chunk's share of transposes / LDS writes rides along with the later steps
+                    constexpr int S0 = KSTEPS / 2;
+                    if (more && s >= S0) stage_store_slice(nxt, s - S0, KSTEPS - S0);
+                }
                 // (steps past the reduction length multiply clamped weights with all-zero activations:
                 // cheaper than a branch, which would force copies of every accumulator)
                 const AStep<SPARSE, TM> &as = a[g % RING];
@@ -465,11 +478,15 @@ void conv_kernel(ConvParams p)
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
                     __builtin_amdgcn_sched_group_barrier(0x100, DSR, 0);    // LDS reads
                     __builtin_amdgcn_sched_group_barrier(0x020, VMR, 0);    // global reads
+                    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);      // transposes of the next chunk (when this step has any)
+                    __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);      // and their LDS writes
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if constexpr (NBUF == 1) __syncthreads();       // everyone is done reading the only copy
-            if (more) stage_store(nxt);
+            if constexpr (NBUF == 1) {
+                __syncthreads();                            // everyone is done reading the only copy
+                if (more) stage_store(nxt);
+            }
             __syncthreads();
         }
     }
@@ -528,7 +545,7 @@ template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MOD
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW>();
+    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW, DEEP>();
     static_assert(smem <= 160 * 1024, "LDS tile too large");
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
