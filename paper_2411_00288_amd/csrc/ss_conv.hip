@@ -103,12 +103,15 @@ struct AStep {
     uint32_t idx[TM];
 };
 
-template <int MODE, int KH, int KW, bool DEEP>
+// KSPLIT wave groups share a workgroup's output tile and split the reduction: a chunk holds KSPLIT
+// runs of KSTEPS steps, one per group.
+template <int MODE, int KH, int KW, bool DEEP, int KSPLIT>
 struct ChunkShape {
     static constexpr int TAPS = KH * KW;
-    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per LDS chunk
-    static constexpr int BK = KSTEPS * 32;
-    static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
+    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per wave group and LDS chunk
+    static constexpr int BK = KSTEPS * 32;             // reduction indices per group and chunk
+    static constexpr int CK = KSPLIT * BK;             // ... per chunk
+    static constexpr int ROW = CK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
     // LDS copies of the chunk: double-buffered, so that the next chunk is written while this one is
     // multiplied -- except for the large unfolded 3x3 chunk in the shallow variant, which is kept once
     // (more workgroups per compute unit then hide the store phase instead).
@@ -128,11 +131,12 @@ constexpr int ring_size(int ksteps, int regs_per_step, int budget)
         if (ksteps % r == 0 || r % ksteps == 0) return r;
 }
 
-template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
+template <int BM, int BN, int MODE, int KH, int KW, bool DEEP, int KSPLIT>
 constexpr size_t smem_bytes()
 {
-    size_t stage = (size_t)ChunkShape<MODE, KH, KW, DEEP>::NBUF * BN * ChunkShape<MODE, KH, KW, DEEP>::ROW * 2;
-    size_t epi = (size_t)BN * (BM * 2 + 8);
+    using CS = ChunkShape<MODE, KH, KW, DEEP, KSPLIT>;
+    size_t stage = (size_t)CS::NBUF * BN * CS::ROW * 2;
+    size_t epi = (size_t)BN * (BM * 2 + 8) + (KSPLIT > 1 ? (size_t)BM * BN * 4 : 0);   // + the partial sums two groups exchange (fp32, half a tile each way)
     return (stage > epi ? stage : epi) + (size_t)BM * 4;      // + the tile's bias values (fp32)
 }
 
@@ -146,13 +150,20 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // DEEP: for grids of at most about one workgroup per compute unit, where no other wave hides
 // latency: weight fragments are prefetched 8+ steps ahead and activation fragments 3 steps ahead
 // (instead of 1), at the price of registers, i.e. of the occupancy such a grid cannot use anyway.
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64)
+// SPEC: four extra waves do nothing but build the activation chunks in LDS (loads two chunks ahead,
+// transposes, LDS writes); the WAVES_M x WAVES_N waves only fetch weights, read LDS and multiply.
+// A wave issues in order, so without this split every wait of the staging code also stalls the
+// wave's matrix instructions.
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, int KSPLIT, bool SPEC>
+__global__ __launch_bounds__((WAVES_M * WAVES_N * KSPLIT + (SPEC ? 4 : 0)) * 64)
 __attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
 void conv_kernel(ConvParams p)
 {
-    using CS = ChunkShape<MODE, KH, KW, DEEP>;
-    constexpr int NT = WAVES_M * WAVES_N * 64;
+    using CS = ChunkShape<MODE, KH, KW, DEEP, KSPLIT>;
+    static_assert(KSPLIT == 1 || (KSPLIT == 2 && TN % 2 == 0), "the two wave groups hand each other half of their column tiles");
+    static_assert(!SPEC || (DEEP && KSPLIT == 1), "producer waves come with the deep variant only");
+    constexpr int NMATH = WAVES_M * WAVES_N * KSPLIT * 64;       // threads that multiply
+    constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int TAPS = CS::TAPS;
@@ -160,12 +171,13 @@ void conv_kernel(ConvParams p)
     // Weight fragments are prefetched RING-1 reduction steps ahead into a register ring, as deep as
     // about 24 (48 when DEEP) VGPRs allow (deeper rings cost occupancy, which the bandwidth-bound layers need more); RING divides the chunk or is a multiple of it (then the chunk loop is
     // unrolled RING/KSTEPS times so that every ring slot is a compile-time register).
-    constexpr int RING = ring_size(KSTEPS, TM * (SPARSE ? 5 : 8), DEEP ? 48 : 24);
+    constexpr int RING = ring_size(KSTEPS, TM * (SPARSE ? 5 : 8), SPEC ? 96 : (DEEP ? 48 : 24));
     constexpr int BD = DEEP ? 4 : 2;                      // activation-fragment ring depth
     constexpr int PF = RING - 1;
     constexpr int UNROLL = RING > KSTEPS ? RING / KSTEPS : 1;
     static_assert(KSTEPS % RING == 0 || RING % KSTEPS == 0, "ring and chunk must nest");
     constexpr int BK = CS::BK;
+    constexpr int CK = CS::CK;
     constexpr int ROW = CS::ROW;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t *Bs0 = smem;
@@ -174,9 +186,12 @@ void conv_kernel(ConvParams p)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave % WAVES_M;
-    const int wn = wave / WAVES_M;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool producer = SPEC && wave >= NMATH / 64;     // wave-uniform
+    const int wv = wave % (WAVES_M * WAVES_N);   // position in the output tile
+    const int kg = KSPLIT == 1 ? 0 : wave / (WAVES_M * WAVES_N);   // reduction group (waves wv and wv + WAVES_M*WAVES_N share a SIMD)
+    const int wm = wv % WAVES_M;
+    const int wn = wv / WAVES_M;
     // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Renumber them so
     // that an XCD works on a contiguous run of tiles: both row tiles of a pixel tile, and pixel tiles
     // that share halo rows, then hit the same L2.
@@ -194,26 +209,28 @@ void conv_kernel(ConvParams p)
 
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
-    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP>() - (size_t)BM * 4));
-    float bias_r[(BM + NT - 1) / NT];
+    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP, KSPLIT>() - (size_t)BM * 4));
+    float bias_r[(BM + NMATH - 1) / NMATH];
 #pragma unroll
-    for (int j = 0; j < (BM + NT - 1) / NT; j++) {
-        const int o = m0 + tid + j * NT;
-        bias_r[j] = (p.bias != nullptr && tid + j * NT < BM && o < p.Cout) ? p.bias[o] : 0.f;
+    for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++) {
+        const int o = m0 + tid + j * NMATH;
+        bias_r[j] = (p.bias != nullptr && tid + j * NMATH < BM && o < p.Cout) ? p.bias[o] : 0.f;
     }
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
-    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8));
-    constexpr int ST = NT < BN * UNITS ? NT : BN * UNITS;     // staging threads (whole waves); the rest only multiply
+    constexpr int UNITS = KSPLIT * ((MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8)));
+    constexpr int ST = SPEC ? (256 < BN * UNITS ? 256 : BN * UNITS) : (NT < BN * UNITS ? NT : BN * UNITS);     // staging threads (whole waves); the rest only multiply
     constexpr int ITEMS = BN * UNITS / ST;
+    constexpr int NSET = SPEC ? 2 : 1;                    // producer waves hold two chunks in registers
     static_assert(BN * UNITS % ST == 0 && ST % UNITS == 0 && ST % 64 == 0 && ITEMS >= 1, "tile/threads mismatch");
-    const bool stager = (ST == NT) || tid < ST;
+    const int stid = SPEC ? tid - NMATH : tid;            // index among the staging threads
+    const bool stager = SPEC ? (producer && stid < ST) : ((ST == NT) || tid < ST);
     // Thread -> (pixel row, unit): unit fastest, so consecutive lanes read consecutive 16-byte pieces of one
     // pixel (coalesced).  (Putting 16 pixel rows of one unit on consecutive lanes makes the transposed LDS
     // writes conflict-free but quadruples the cache lines per load instruction: measured 30-40 % slower.)
-    const int unit = tid % UNITS;
-    const int pr0 = (tid % ST) / UNITS;
+    const int unit = (stid & 0xFFFF) % UNITS;
+    const int pr0 = ((stid & 0xFFFF) % ST) / UNITS;
     unsigned pixbyte[ITEMS];          // byte offset of x[n, ho*sh-ph, wo*sw-pw, 0] (wraps below 0 for padded pixels)
     int ih0[ITEMS], iw0[ITEMS];
 #pragma unroll
@@ -269,12 +286,15 @@ void conv_kernel(ConvParams p)
         }
     }
 
-    u32x4 stage_v[(MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
-    uint16_t stage_g[MODE == MODE_GATHER ? ITEMS : 1][4];
-    u32x4 stage_t[MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
+    u32x4 stage_v_[NSET][(MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
+    uint16_t stage_g_[NSET][MODE == MODE_GATHER ? ITEMS : 1][4];
+    u32x4 stage_t_[NSET][MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
-    auto stage_load = [&](int ci) {
+    auto stage_load = [&](int ci, int set = 0) {      // set: compile time at every call site
         if (!stager) return;
+        auto &stage_v = stage_v_[set];
+        auto &stage_g = stage_g_[set];
+        auto &stage_t = stage_t_[set];
         if constexpr (MODE == MODE_VEC) {
             const unsigned koff = vk < p.K ? (unsigned)(((vr * p.W + vt) * p.Cin + vc) * 2) : kOutOfRange;
 #pragma unroll
@@ -284,23 +304,23 @@ void conv_kernel(ConvParams p)
                 unsigned off = ok ? pixbyte[i] + koff : kOutOfRange;
                 stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
             }
-            vk += BK;
-            vc += BK;
+            vk += CK;
+            vc += CK;
             while (vc >= p.Cin) {
                 vc -= p.Cin;
                 if (++vt == p.kw) { vt = 0; ++vr; }
             }
         } else if constexpr (MODE == MODE_PW || MODE == MODE_PW2) {
-            const bool kok = ci * BK + unit * 8 < p.K;      // the last chunk may reach past the reduction length
+            const bool kok = ci * CK + unit * 8 < p.K;      // the last chunk may reach past the reduction length
 #pragma unroll
             for (int i = 0; i < ITEMS; i++)
-                stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(kok ? pwoff[i] : kOutOfRange), ci * (BK * 2), 0);
+                stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(kok ? pwoff[i] : kOutOfRange), ci * (CK * 2), 0);
         } else if constexpr (MODE == MODE_GATHER) {
             unsigned off[4];
             int er[4], et[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                int k = ci * BK + unit * 4 + e;
+                int k = ci * CK + unit * 4 + e;
                 int c, r, t;
                 if (p.korder == SS_K_CRS) {
                     int khw = p.kh * p.kw;
@@ -329,7 +349,7 @@ void conv_kernel(ConvParams p)
                 }
             }
         } else {
-            const int soff = ci * 64;                   // 32 channels per chunk
+            const int soff = ci * (64 * KSPLIT);        // 32 channels per group and chunk (the host checks cin % (32*KSPLIT) == 0)
 #pragma unroll
             for (int i = 0; i < ITEMS; i++)
 #pragma unroll
@@ -339,8 +359,11 @@ void conv_kernel(ConvParams p)
     };
     // Writes slice j of n of the staged chunk to LDS (j, n are compile-time at every call site): a share of the
     // transposed 16-byte vectors (tap mode) or of the items (other modes).  stage_store = all of it.
-    auto stage_store_slice = [&](uint16_t *Bs, int j, int n) {
+    auto stage_store_slice = [&](uint16_t *Bs, int j, int n, int set = 0) {
         if (!stager) return;
+        auto &stage_v = stage_v_[set];
+        auto &stage_g = stage_g_[set];
+        auto &stage_t = stage_t_[set];
 #pragma unroll
         for (int i = 0; i < ITEMS; i++) {
             int pr = pr0 + i * (ST / UNITS);
@@ -377,7 +400,7 @@ void conv_kernel(ConvParams p)
             }
         }
     };
-    auto stage_store = [&](uint16_t *Bs) { stage_store_slice(Bs, 0, 1); };
+    auto stage_store = [&](uint16_t *Bs, int set = 0) { stage_store_slice(Bs, 0, 1, set); };
 
     // ------------------------------------------------------------------ weight fragments
     // Row tiles past the last one are clamped to it (their rows are never stored); reduction steps
@@ -395,8 +418,9 @@ void conv_kernel(ConvParams p)
         for (int tm = 0; tm < TM; tm++) {
             if constexpr (SPARSE) {
                 a.v[0][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 1024, 0);
-                uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rm, (int)m_voff[tm], (ks >> 1) * 256, 0);
-                a.idx[tm] = (ks & 1) ? (w >> 16) : w;    // the instruction reads index bits [15:0]
+                // The index word of the step pair; the step's half is shifted down where it is used, steps later (a
+                // shift here would have to wait for the load it follows and stall the wave at every step).
+                a.idx[tm] = __builtin_amdgcn_raw_buffer_load_b32(rm, (int)m_voff[tm], (ks >> 1) * 256, 0);
             } else {
                 a.v[0][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 2048, 0);
                 a.v[1][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 2048 + 1024, 0);
@@ -413,15 +437,38 @@ void conv_kernel(ConvParams p)
             for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0.f;
 
     // ------------------------------------------------------------------ main loop (double-buffered LDS, ring of weight steps)
-    const int nchunks = (p.Ks + KSTEPS - 1) / KSTEPS;
+    const int nchunks = (p.Ks + KSPLIT * KSTEPS - 1) / (KSPLIT * KSTEPS);
+    // reduction step of this wave's step s of chunk ci (s may run past the chunk: prefetch)
+    auto step_of = [&](int ci, int s) { return (ci + s / KSTEPS) * (KSPLIT * KSTEPS) + kg * KSTEPS + s % KSTEPS; };
     AStep<SPARSE, TM> a[RING];
-    stage_load(0);
+    if constexpr (SPEC) {
+        if (producer) {
+            // ---- producer waves: chunk ci+1 is written to LDS while the others multiply chunk ci; its loads were
+            // issued one chunk earlier.  One barrier per chunk, exactly as in the multiplying waves' loop below.
+            stage_load(0, 0);
+            if (nchunks > 1) stage_load(1, 1);
+            stage_store(Bs0, 0);
+            __syncthreads();
+            for (int c0 = 0; c0 < nchunks; c0 += 2) {
 #pragma unroll
-    for (int s = 0; s < PF; s++) load_a(a[s], s);
-    stage_store(Bs0);
+                for (int u = 0; u < 2; u++) {
+                    const int ci = c0 + u;
+                    if (ci >= nchunks) break;               // uniform
+                    if (ci + 2 < nchunks) stage_load(ci + 2, u);            // set u held chunk ci, which is in LDS already
+                    if (ci + 1 < nchunks) stage_store(u ? Bs0 : Bs1, 1 - u);
+                    __syncthreads();
+                }
+            }
+        }
+    }
+    if (!producer) {
+    if constexpr (!SPEC) stage_load(0);
 #pragma unroll
-    for (int j = 0; j < (BM + NT - 1) / NT; j++)
-        if (tid + j * NT < BM) bias_s[tid + j * NT] = bias_r[j];
+    for (int s = 0; s < PF; s++) load_a(a[s], step_of(0, s));
+    if constexpr (!SPEC) stage_store(Bs0);
+#pragma unroll
+    for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++)
+        if (tid + j * NMATH < BM) bias_s[tid + j * NMATH] = bias_r[j];
     __syncthreads();
     for (int c0 = 0; c0 < nchunks; c0 += UNROLL) {
 #pragma unroll
@@ -431,13 +478,14 @@ void conv_kernel(ConvParams p)
             const uint16_t *cur = (ci & 1) ? Bs1 : Bs0;
             uint16_t *nxt = (ci & 1) ? Bs0 : Bs1;
             const bool more = ci + 1 < nchunks;
-            if (more) stage_load(ci + 1);
+            if constexpr (!SPEC)
+                if (more) stage_load(ci + 1);
             __builtin_amdgcn_sched_barrier(0);
             B32 b[BD][TN];
             auto load_b = [&](B32 (&bf)[TN], int s) {
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
-                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
+                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + kg * BK + s * 32 + 16 * (lane >> 5);
                     bf[tn].lo = *reinterpret_cast<const u32x4 *>(src);
                     bf[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
                 }
@@ -447,21 +495,22 @@ void conv_kernel(ConvParams p)
 #pragma unroll
             for (int s = 0; s < KSTEPS; s++) {
                 const int g = u * KSTEPS + s;               // position in the ring (compile time)
-                load_a(a[(g + PF) % RING], ci * KSTEPS + s + PF);
+                load_a(a[(g + PF) % RING], step_of(ci, s + PF));
                 if (s + BD - 1 < KSTEPS) load_b(b[(s + BD - 1) % BD], s + BD - 1);   // later steps' activations while this step multiplies
-                if constexpr (NBUF == 2) {          // the next chunk's share of transposes / LDS writes rides along with the later steps
+                if constexpr (NBUF == 2 && !SPEC) {          // the next chunk's share of transposes / LDS writes rides along with the later steps
                     constexpr int S0 = KSTEPS / 2;
                     if (more && s >= S0) stage_store_slice(nxt, s - S0, KSTEPS - S0);
                 }
                 // (steps past the reduction length multiply clamped weights with all-zero activations:
                 // cheaper than a branch, which would force copies of every accumulator)
                 const AStep<SPARSE, TM> &as = a[g % RING];
+                const int idx_shift = (min(step_of(ci, s), p.Ks - 1) & 1) * 16;      // the instruction reads index bits [15:0]
 #pragma unroll
                 for (int tm = 0; tm < TM; tm++)
 #pragma unroll
                     for (int tn = 0; tn < TN; tn++) {
                         if constexpr (SPARSE) {
-                            acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s % BD][tn], acc[tm][tn], as.idx[tm]);
+                            acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s % BD][tn], acc[tm][tn], as.idx[tm] >> idx_shift);
                         } else {
                             acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[s % BD][tn].lo, acc[tm][tn]);
                             acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[s % BD][tn].hi, acc[tm][tn]);
@@ -490,13 +539,55 @@ void conv_kernel(ConvParams p)
             __syncthreads();
         }
     }
+    }   // !producer
 
     // ------------------------------------------------------------------ epilogue
     // bias + activation in fp32, one rounding to the 16-bit type, then through LDS so that every
     // pixel's run of BM output channels leaves as 16-byte, fully coalesced NHWC stores.
     const float relu_floor = p.act == SS_ACT_RELU ? 0.f : -__builtin_inff();
     constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
-    uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier
+    constexpr int TNE = TN / KSPLIT;                   // column tiles this wave finishes
+    constexpr int XBYTES = KSPLIT > 1 ? BM * BN * 4 : 0;     // exchanged partial sums: every wave gives half of its fp32 tile
+    uint16_t *Cs = smem + XBYTES / 2;   // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
+    if constexpr (KSPLIT == 2) {
+        // Group g keeps column tiles [g*TNE, (g+1)*TNE) and hands its partial sums of the others to its partner
+        // wave (same wv, other group) through LDS; the kept tiles move to the front of acc.
+        float *X = reinterpret_cast<float *>(smem);
+        float *give_p = X + (size_t)((wv * 2 + kg) * TM * TNE * 16) * 64 + lane * 4;
+        const float *take_p = X + (size_t)((wv * 2 + (kg ^ 1)) * TM * TNE * 16) * 64 + lane * 4;
+#pragma unroll
+        for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+            for (int t = 0; t < TNE; t++) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    float give[4], keep[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const float lo = acc[tm][t][4 * q + e], hi = acc[tm][TNE + t][4 * q + e];
+                        give[e] = kg ? lo : hi;
+                        keep[e] = kg ? hi : lo;
+                    }
+                    *reinterpret_cast<float4 *>(give_p + ((tm * TNE + t) * 4 + q) * 256) = make_float4(give[0], give[1], give[2], give[3]);
+#pragma unroll
+                    for (int e = 0; e < 4; e++) acc[tm][t][4 * q + e] = keep[e];
+                }
+            }
+        __syncthreads();
+#pragma unroll
+        for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+            for (int t = 0; t < TNE; t++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const float4 got = *reinterpret_cast<const float4 *>(take_p + ((tm * TNE + t) * 4 + q) * 256);
+                    acc[tm][t][4 * q + 0] += got.x;
+                    acc[tm][t][4 * q + 1] += got.y;
+                    acc[tm][t][4 * q + 2] += got.z;
+                    acc[tm][t][4 * q + 3] += got.w;
+                }
+    }
+    if (!producer)
 #pragma unroll
     for (int tm = 0; tm < TM; tm++) {
 #pragma unroll
@@ -505,14 +596,14 @@ void conv_kernel(ConvParams p)
             const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
             const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
 #pragma unroll
-            for (int tn = 0; tn < TN; tn++) {
+            for (int tn = 0; tn < TNE; tn++) {
                 float r[4];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     float v = acc[tm][tn][4 * q + e] + bv[e];
                     r[e] = v < relu_floor ? 0.f : v;      // ReLU when relu_floor = 0, identity when -inf; NaN passes through
                 }
-                const int pl = (wn * TN + tn) * 32 + (lane & 31);
+                const int pl = (wn * TN + kg * TNE + tn) * 32 + (lane & 31);
                 *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
             }
         }
@@ -541,18 +632,19 @@ void conv_kernel(ConvParams p)
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false>
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false, int KSPLIT = 1, bool SPEC = false>
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW, DEEP>();
+    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW, DEEP, KSPLIT>();
+    if (MODE == MODE_TAPS && p0.Cin % (32 * KSPLIT) != 0) return SS_ERR_INVALID_ARG;   // a chunk is 32*KSPLIT whole channels
     static_assert(smem <= 160 * 1024, "LDS tile too large");
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
-    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP>;
+    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, KSPLIT, SPEC>;
     if (smem > 64 * 1024) {
         static bool attr_set = false;    // once per process: raises this kernel's dynamic-LDS limit
         if (!attr_set) {
@@ -562,7 +654,7 @@ static int launch(const ConvParams &p0, hipStream_t s)
             attr_set = true;
         }
     }
-    kern<<<dim3((unsigned)blocks), dim3(WAVES_M * WAVES_N * 64), smem, s>>>(p);
+    kern<<<dim3((unsigned)blocks), dim3((WAVES_M * WAVES_N * KSPLIT + (SPEC ? 4 : 0)) * 64), smem, s>>>(p);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
 }
 
@@ -575,6 +667,8 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
 //   id 0:  64 x  64 (2x2 waves, 1x1)       id 1: same, deep
 //   id 2: 128 x  64 (4x1 waves, 1x2)       id 3: same, deep
 //   id 4: 256 x  64 (4x1 waves, 2x2)       id 5: same, deep
+//   id 6: as 3, id 7: as 5, with two wave groups (8 waves) that split the reduction of the tile
+//   id 8: as 3, id 9: as 5, plus four producer waves that build the activation chunks
 // Layouts with all four waves along the output channels fetch no weight tile twice inside a
 // workgroup; 2x2 layouts of the same tile sizes, 8-wave workgroups, 128x128 and 256x128 tiles were
 // measured and lost everywhere, so they are not instantiated.
@@ -588,6 +682,10 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
         case 3: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true>(p, s);
         case 4: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, false>(p, s);
         case 5: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true>(p, s);
+        case 6: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, 2>(p, s);
+        case 7: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, 2>(p, s);
+        case 8: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, 1, true>(p, s);
+        case 9: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, 1, true>(p, s);
         default: break;
     }
     return SS_ERR_INVALID_ARG;
