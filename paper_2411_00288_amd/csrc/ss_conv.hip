@@ -43,7 +43,23 @@ struct ConvParams {
     int N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, Ho, Wo, P, K, Ks, Kp, Mt, act, korder;
     int tiles_m;
     unsigned x_bytes, a_bytes, meta_bytes;
+    // division by Ho*Wo, Wo and tiles_m as multiply + shift (see fast_div)
+    unsigned howo_mul, howo_sh, wo_mul, wo_sh, tm_mul, tm_sh;
 };
+
+// floor(n / d) for 0 <= n < 2^31 as (n * mul) >> sh with s = ceil(log2 d), sh = 31 + s, mul = ceil(2^sh / d):
+// mul * d - 2^sh < d <= 2^s, so the product overshoots n / d by less than 1 / d, never reaching the next integer.
+static inline void fast_div_setup(unsigned d, unsigned *mul, unsigned *sh)
+{
+    unsigned s = 0;
+    while ((1ull << s) < d) s++;
+    *sh = 31 + s;
+    *mul = (unsigned)(((1ull << (31 + s)) + d - 1) / d);
+}
+__device__ __forceinline__ int fast_div(int n, unsigned mul, unsigned sh)
+{
+    return (int)(((unsigned long long)(unsigned)n * mul) >> sh);
+}
 
 constexpr unsigned kOutOfRange = 0x80000000u;   // >= any buffer size used here: the load returns 0
 constexpr int kRsrcFlags = 0x00020000;          // raw buffer, 32-bit data format (gfx9 family)
@@ -161,7 +177,7 @@ void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP, KSPLIT>;
     static_assert(KSPLIT == 1 || (KSPLIT == 2 && TN % 2 == 0), "the two wave groups hand each other half of their column tiles");
-    static_assert(!SPEC || (DEEP && KSPLIT == 1), "producer waves come with the deep variant only");
+    static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
     constexpr int NMATH = WAVES_M * WAVES_N * KSPLIT * 64;       // threads that multiply
     constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
@@ -197,8 +213,8 @@ void conv_kernel(ConvParams p)
     // that share halo rows, then hit the same L2.
     const int nb = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int lid = xcd * (nb >> 3) + min(xcd, nb & 7) + slot;
-    const int tile_m = lid % p.tiles_m;
-    const int tile_n = lid / p.tiles_m;
+    const int tile_n = fast_div(lid, p.tm_mul, p.tm_sh);
+    const int tile_m = lid - tile_n * p.tiles_m;
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
     const int HoWo = p.Ho * p.Wo;
@@ -210,12 +226,16 @@ void conv_kernel(ConvParams p)
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
     float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP, KSPLIT>() - (size_t)BM * 4));
+    // (Loaded after the first activation / weight loads are on their way: issued first, its latency would
+    // sit in front of everything else.)
     float bias_r[(BM + NMATH - 1) / NMATH];
+    auto load_bias = [&]() {
 #pragma unroll
-    for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++) {
-        const int o = m0 + tid + j * NMATH;
-        bias_r[j] = (p.bias != nullptr && tid + j * NMATH < BM && o < p.Cout) ? p.bias[o] : 0.f;
-    }
+        for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++) {
+            const int o = m0 + tid + j * NMATH;
+            bias_r[j] = (p.bias != nullptr && tid + j * NMATH < BM && o < p.Cout) ? p.bias[o] : 0.f;
+        }
+    };
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
@@ -225,7 +245,8 @@ void conv_kernel(ConvParams p)
     constexpr int NSET = SPEC ? 2 : 1;                    // producer waves hold two chunks in registers
     static_assert(BN * UNITS % ST == 0 && ST % UNITS == 0 && ST % 64 == 0 && ITEMS >= 1, "tile/threads mismatch");
     const int stid = SPEC ? tid - NMATH : tid;            // index among the staging threads
-    const bool stager = SPEC ? (producer && stid < ST) : ((ST == NT) || tid < ST);
+    static_assert(!SPEC || ST == 256, "every producer thread stages");
+    const bool stager = SPEC ? true : ((ST == NT) || tid < ST);     // (producer waves: only they call the staging code)
     // Thread -> (pixel row, unit): unit fastest, so consecutive lanes read consecutive 16-byte pieces of one
     // pixel (coalesced).  (Putting 16 pixel rows of one unit on consecutive lanes makes the transposed LDS
     // writes conflict-free but quadruples the cache lines per load instruction: measured 30-40 % slower.)
@@ -238,9 +259,9 @@ void conv_kernel(ConvParams p)
         int pr = pr0 + i * (ST / UNITS);
         int pg = n0 + pr;
         if (pg < p.P) {
-            int n = pg / HoWo;
+            int n = fast_div(pg, p.howo_mul, p.howo_sh);
             int rem = pg - n * HoWo;
-            int ho = rem / p.Wo;
+            int ho = fast_div(rem, p.wo_mul, p.wo_sh);
             int wo = rem - ho * p.Wo;
             ih0[i] = ho * p.sh - p.ph;
             iw0[i] = wo * p.sw - p.pw;
@@ -445,19 +466,33 @@ void conv_kernel(ConvParams p)
         if (producer) {
             // ---- producer waves: chunk ci+1 is written to LDS while the others multiply chunk ci; its loads were
             // issued one chunk earlier.  One barrier per chunk, exactly as in the multiplying waves' loop below.
+            // The steady-state loop issues its loads unconditionally: behind a condition, the compiler's wait before
+            // the LDS writes must also cover the path without new loads, and so waits for the new loads as well
+            // (a full memory latency per chunk).
             stage_load(0, 0);
-            if (nchunks > 1) stage_load(1, 1);
             stage_store(Bs0, 0);
+            if (nchunks > 1) stage_load(1, 1);
             __syncthreads();
-            for (int c0 = 0; c0 < nchunks; c0 += 2) {
-#pragma unroll
-                for (int u = 0; u < 2; u++) {
-                    const int ci = c0 + u;
-                    if (ci >= nchunks) break;               // uniform
-                    if (ci + 2 < nchunks) stage_load(ci + 2, u);            // set u held chunk ci, which is in LDS already
-                    if (ci + 1 < nchunks) stage_store(u ? Bs0 : Bs1, 1 - u);
+            // the last two chunks: nothing left to load (set, buf: where chunk ci + 1 waits and where it goes)
+            auto tail = [&](int ci, int set, uint16_t *buf) {
+                if (ci + 1 < nchunks) {
+                    stage_store(buf, set);
                     __syncthreads();
+                    ci++;
                 }
+                if (ci < nchunks) __syncthreads();
+            };
+            for (int ci = 0;;) {
+                if (ci + 2 >= nchunks) { tail(ci, 1, Bs1); break; }
+                stage_load(ci + 2, 0);                      // set 0 held chunk ci, which is in LDS already
+                stage_store(Bs1, 1);
+                __syncthreads();
+                ci++;
+                if (ci + 2 >= nchunks) { tail(ci, 0, Bs0); break; }
+                stage_load(ci + 2, 1);
+                stage_store(Bs0, 0);
+                __syncthreads();
+                ci++;
             }
         }
     }
@@ -465,6 +500,7 @@ void conv_kernel(ConvParams p)
     if constexpr (!SPEC) stage_load(0);
 #pragma unroll
     for (int s = 0; s < PF; s++) load_a(a[s], step_of(0, s));
+    load_bias();
     if constexpr (!SPEC) stage_store(Bs0);
 #pragma unroll
     for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++)
@@ -555,6 +591,7 @@ void conv_kernel(ConvParams p)
         float *X = reinterpret_cast<float *>(smem);
         float *give_p = X + (size_t)((wv * 2 + kg) * TM * TNE * 16) * 64 + lane * 4;
         const float *take_p = X + (size_t)((wv * 2 + (kg ^ 1)) * TM * TNE * 16) * 64 + lane * 4;
+        if (!producer)
 #pragma unroll
         for (int tm = 0; tm < TM; tm++)
 #pragma unroll
@@ -574,6 +611,7 @@ void conv_kernel(ConvParams p)
                 }
             }
         __syncthreads();
+        if (!producer)
 #pragma unroll
         for (int tm = 0; tm < TM; tm++)
 #pragma unroll
@@ -641,6 +679,7 @@ static int launch(const ConvParams &p0, hipStream_t s)
     static_assert(smem <= 160 * 1024, "LDS tile too large");
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
+    fast_div_setup((unsigned)p.tiles_m, &p.tm_mul, &p.tm_sh);
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
@@ -669,6 +708,9 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
 //   id 4: 256 x  64 (4x1 waves, 2x2)       id 5: same, deep
 //   id 6: as 3, id 7: as 5, with two wave groups (8 waves) that split the reduction of the tile
 //   id 8: as 3, id 9: as 5, plus four producer waves that build the activation chunks
+//   id 10: 128 x 64 as 2x1 waves of 2x2 tiles in two reduction groups, plus producer waves: half the LDS reads
+//          of id 8 (a wave's activation fragments serve two row tiles) for the same weight traffic
+//   id 11: 128 x 64 as 2x1 waves of 2x2 tiles plus producer waves: the same saving with two multiplying waves
 // Layouts with all four waves along the output channels fetch no weight tile twice inside a
 // workgroup; 2x2 layouts of the same tile sizes, 8-wave workgroups, 128x128 and 256x128 tiles were
 // measured and lost everywhere, so they are not instantiated.
@@ -686,6 +728,8 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
         case 7: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, 2>(p, s);
         case 8: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, 1, true>(p, s);
         case 9: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, 1, true>(p, s);
+        case 10: return launch<DT, SPARSE, 2, 1, 2, 2, MODE, KH, KW, true, 2, true>(p, s);
+        case 11: return launch<DT, SPARSE, 2, 1, 2, 2, MODE, KH, KW, true, 1, true>(p, s);
         default: break;
     }
     return SS_ERR_INVALID_ARG;
@@ -765,6 +809,9 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.Ho = Ho; p.Wo = Wo; p.P = (int)P;
     p.K = t.K; p.Ks = t.Ks; p.Kp = t.Kp; p.Mt = t.Mt; p.act = act; p.korder = desc->korder;
     p.tiles_m = 0;
+    p.tm_mul = p.tm_sh = 0;
+    fast_div_setup((unsigned)(Ho * Wo), &p.howo_mul, &p.howo_sh);
+    fast_div_setup((unsigned)Wo, &p.wo_mul, &p.wo_sh);
     p.x_bytes = (unsigned)xbytes;
     p.a_bytes = (unsigned)((size_t)t.Mt * t.Ks * (SPARSE ? 1024 : 2048));
     p.meta_bytes = SPARSE ? (unsigned)((size_t)t.Mt * t.Kp * 256) : 4u;

@@ -15,7 +15,7 @@ from helpers import check_close, oracle_ref, run_gpu
 
 pytestmark = pytest.mark.gpu
 
-TILE_IDS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9]
+TILE_IDS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]
 
 
 def _L(N, H, W, cin, cout, k, s=1, p=0, dtype=wl.F16, korder=wl.K_CRS, seed=0):
