@@ -119,15 +119,12 @@ struct AStep {
     uint32_t idx[TM];
 };
 
-// KSPLIT wave groups share a workgroup's output tile and split the reduction: a chunk holds KSPLIT
-// runs of KSTEPS steps, one per group.
-template <int MODE, int KH, int KW, bool DEEP, int KSPLIT>
+template <int MODE, int KH, int KW, bool DEEP>
 struct ChunkShape {
     static constexpr int TAPS = KH * KW;
-    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per wave group and LDS chunk
-    static constexpr int BK = KSTEPS * 32;             // reduction indices per group and chunk
-    static constexpr int CK = KSPLIT * BK;             // ... per chunk
-    static constexpr int ROW = CK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
+    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per LDS chunk
+    static constexpr int BK = KSTEPS * 32;
+    static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
     // LDS copies of the chunk: double-buffered, so that the next chunk is written while this one is
     // multiplied -- except for the large unfolded 3x3 chunk in the shallow variant, which is kept once
     // (more workgroups per compute unit then hide the store phase instead).
@@ -147,12 +144,12 @@ constexpr int ring_size(int ksteps, int regs_per_step, int budget)
         if (ksteps % r == 0 || r % ksteps == 0) return r;
 }
 
-template <int BM, int BN, int MODE, int KH, int KW, bool DEEP, int KSPLIT>
+template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
 constexpr size_t smem_bytes()
 {
-    using CS = ChunkShape<MODE, KH, KW, DEEP, KSPLIT>;
+    using CS = ChunkShape<MODE, KH, KW, DEEP>;
     size_t stage = (size_t)CS::NBUF * BN * CS::ROW * 2;
-    size_t epi = (size_t)BN * (BM * 2 + 8) + (KSPLIT > 1 ? (size_t)BM * BN * 4 : 0);   // + the partial sums two groups exchange (fp32, half a tile each way)
+    size_t epi = (size_t)BN * (BM * 2 + 8);
     return (stage > epi ? stage : epi) + (size_t)BM * 4;      // + the tile's bias values (fp32)
 }
 
@@ -170,15 +167,14 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // transposes, LDS writes); the WAVES_M x WAVES_N waves only fetch weights, read LDS and multiply.
 // A wave issues in order, so without this split every wait of the staging code also stalls the
 // wave's matrix instructions.
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, int KSPLIT, bool SPEC>
-__global__ __launch_bounds__((WAVES_M * WAVES_N * KSPLIT + (SPEC ? 4 : 0)) * 64)
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC>
+__global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
 __attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
 void conv_kernel(ConvParams p)
 {
-    using CS = ChunkShape<MODE, KH, KW, DEEP, KSPLIT>;
-    static_assert(KSPLIT == 1 || (KSPLIT == 2 && TN % 2 == 0), "the two wave groups hand each other half of their column tiles");
+    using CS = ChunkShape<MODE, KH, KW, DEEP>;
     static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
-    constexpr int NMATH = WAVES_M * WAVES_N * KSPLIT * 64;       // threads that multiply
+    constexpr int NMATH = WAVES_M * WAVES_N * 64;         // threads that multiply
     constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
     constexpr int BN = WAVES_N * TN * 32;
@@ -193,7 +189,6 @@ void conv_kernel(ConvParams p)
     constexpr int UNROLL = RING > KSTEPS ? RING / KSTEPS : 1;
     static_assert(KSTEPS % RING == 0 || RING % KSTEPS == 0, "ring and chunk must nest");
     constexpr int BK = CS::BK;
-    constexpr int CK = CS::CK;
     constexpr int ROW = CS::ROW;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t *Bs0 = smem;
@@ -204,10 +199,8 @@ void conv_kernel(ConvParams p)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool producer = SPEC && wave >= NMATH / 64;     // wave-uniform
-    const int wv = wave % (WAVES_M * WAVES_N);   // position in the output tile
-    const int kg = KSPLIT == 1 ? 0 : wave / (WAVES_M * WAVES_N);   // reduction group (waves wv and wv + WAVES_M*WAVES_N share a SIMD)
-    const int wm = wv % WAVES_M;
-    const int wn = wv / WAVES_M;
+    const int wm = wave % WAVES_M;               // (producer waves: unused)
+    const int wn = (wave / WAVES_M) % WAVES_N;
     // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Renumber them so
     // that an XCD works on a contiguous run of tiles: both row tiles of a pixel tile, and pixel tiles
     // that share halo rows, then hit the same L2.
@@ -225,7 +218,7 @@ void conv_kernel(ConvParams p)
 
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
-    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP, KSPLIT>() - (size_t)BM * 4));
+    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP>() - (size_t)BM * 4));
     // (Loaded after the first activation / weight loads are on their way: issued first, its latency would
     // sit in front of everything else.)
     float bias_r[(BM + NMATH - 1) / NMATH];
@@ -239,7 +232,7 @@ void conv_kernel(ConvParams p)
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
-    constexpr int UNITS = KSPLIT * ((MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8)));
+    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8));
     constexpr int ST = SPEC ? (256 < BN * UNITS ? 256 : BN * UNITS) : (NT < BN * UNITS ? NT : BN * UNITS);     // staging threads (whole waves); the rest only multiply
     constexpr int ITEMS = BN * UNITS / ST;
     constexpr int NSET = SPEC ? 2 : 1;                    // producer waves hold two chunks in registers
@@ -325,23 +318,23 @@ void conv_kernel(ConvParams p)
                 unsigned off = ok ? pixbyte[i] + koff : kOutOfRange;
                 stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
             }
-            vk += CK;
-            vc += CK;
+            vk += BK;
+            vc += BK;
             while (vc >= p.Cin) {
                 vc -= p.Cin;
                 if (++vt == p.kw) { vt = 0; ++vr; }
             }
         } else if constexpr (MODE == MODE_PW || MODE == MODE_PW2) {
-            const bool kok = ci * CK + unit * 8 < p.K;      // the last chunk may reach past the reduction length
+            const bool kok = ci * BK + unit * 8 < p.K;      // the last chunk may reach past the reduction length
 #pragma unroll
             for (int i = 0; i < ITEMS; i++)
-                stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(kok ? pwoff[i] : kOutOfRange), ci * (CK * 2), 0);
+                stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(kok ? pwoff[i] : kOutOfRange), ci * (BK * 2), 0);
         } else if constexpr (MODE == MODE_GATHER) {
             unsigned off[4];
             int er[4], et[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                int k = ci * CK + unit * 4 + e;
+                int k = ci * BK + unit * 4 + e;
                 int c, r, t;
                 if (p.korder == SS_K_CRS) {
                     int khw = p.kh * p.kw;
@@ -370,7 +363,7 @@ void conv_kernel(ConvParams p)
                 }
             }
         } else {
-            const int soff = ci * (64 * KSPLIT);        // 32 channels per group and chunk (the host checks cin % (32*KSPLIT) == 0)
+            const int soff = ci * 64;                   // 32 channels per chunk
 #pragma unroll
             for (int i = 0; i < ITEMS; i++)
 #pragma unroll
@@ -458,9 +451,7 @@ void conv_kernel(ConvParams p)
             for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0.f;
 
     // ------------------------------------------------------------------ main loop (double-buffered LDS, ring of weight steps)
-    const int nchunks = (p.Ks + KSPLIT * KSTEPS - 1) / (KSPLIT * KSTEPS);
-    // reduction step of this wave's step s of chunk ci (s may run past the chunk: prefetch)
-    auto step_of = [&](int ci, int s) { return (ci + s / KSTEPS) * (KSPLIT * KSTEPS) + kg * KSTEPS + s % KSTEPS; };
+    const int nchunks = (p.Ks + KSTEPS - 1) / KSTEPS;
     AStep<SPARSE, TM> a[RING];
     if constexpr (SPEC) {
         if (producer) {
@@ -499,7 +490,7 @@ void conv_kernel(ConvParams p)
     if (!producer) {
     if constexpr (!SPEC) stage_load(0);
 #pragma unroll
-    for (int s = 0; s < PF; s++) load_a(a[s], step_of(0, s));
+    for (int s = 0; s < PF; s++) load_a(a[s], s);
     load_bias();
     if constexpr (!SPEC) stage_store(Bs0);
 #pragma unroll
@@ -521,7 +512,7 @@ void conv_kernel(ConvParams p)
             auto load_b = [&](B32 (&bf)[TN], int s) {
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
-                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + kg * BK + s * 32 + 16 * (lane >> 5);
+                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
                     bf[tn].lo = *reinterpret_cast<const u32x4 *>(src);
                     bf[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
                 }
@@ -531,7 +522,7 @@ void conv_kernel(ConvParams p)
 #pragma unroll
             for (int s = 0; s < KSTEPS; s++) {
                 const int g = u * KSTEPS + s;               // position in the ring (compile time)
-                load_a(a[(g + PF) % RING], step_of(ci, s + PF));
+                load_a(a[(g + PF) % RING], ci * KSTEPS + s + PF);
                 if (s + BD - 1 < KSTEPS) load_b(b[(s + BD - 1) % BD], s + BD - 1);   // later steps' activations while this step multiplies
                 if constexpr (NBUF == 2 && !SPEC) {          // the next chunk's share of transposes / LDS writes rides along with the later steps
                     constexpr int S0 = KSTEPS / 2;
@@ -540,7 +531,7 @@ void conv_kernel(ConvParams p)
                 // (steps past the reduction length multiply clamped weights with all-zero activations:
                 // cheaper than a branch, which would force copies of every accumulator)
                 const AStep<SPARSE, TM> &as = a[g % RING];
-                const int idx_shift = (min(step_of(ci, s), p.Ks - 1) & 1) * 16;      // the instruction reads index bits [15:0]
+                const int idx_shift = (min(ci * KSTEPS + s, p.Ks - 1) & 1) * 16;      // the instruction reads index bits [15:0]
 #pragma unroll
                 for (int tm = 0; tm < TM; tm++)
 #pragma unroll
@@ -582,49 +573,7 @@ void conv_kernel(ConvParams p)
     // pixel's run of BM output channels leaves as 16-byte, fully coalesced NHWC stores.
     const float relu_floor = p.act == SS_ACT_RELU ? 0.f : -__builtin_inff();
     constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
-    constexpr int TNE = TN / KSPLIT;                   // column tiles this wave finishes
-    constexpr int XBYTES = KSPLIT > 1 ? BM * BN * 4 : 0;     // exchanged partial sums: every wave gives half of its fp32 tile
-    uint16_t *Cs = smem + XBYTES / 2;   // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
-    if constexpr (KSPLIT == 2) {
-        // Group g keeps column tiles [g*TNE, (g+1)*TNE) and hands its partial sums of the others to its partner
-        // wave (same wv, other group) through LDS; the kept tiles move to the front of acc.
-        float *X = reinterpret_cast<float *>(smem);
-        float *give_p = X + (size_t)((wv * 2 + kg) * TM * TNE * 16) * 64 + lane * 4;
-        const float *take_p = X + (size_t)((wv * 2 + (kg ^ 1)) * TM * TNE * 16) * 64 + lane * 4;
-        if (!producer)
-#pragma unroll
-        for (int tm = 0; tm < TM; tm++)
-#pragma unroll
-            for (int t = 0; t < TNE; t++) {
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    float give[4], keep[4];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const float lo = acc[tm][t][4 * q + e], hi = acc[tm][TNE + t][4 * q + e];
-                        give[e] = kg ? lo : hi;
-                        keep[e] = kg ? hi : lo;
-                    }
-                    *reinterpret_cast<float4 *>(give_p + ((tm * TNE + t) * 4 + q) * 256) = make_float4(give[0], give[1], give[2], give[3]);
-#pragma unroll
-                    for (int e = 0; e < 4; e++) acc[tm][t][4 * q + e] = keep[e];
-                }
-            }
-        __syncthreads();
-        if (!producer)
-#pragma unroll
-        for (int tm = 0; tm < TM; tm++)
-#pragma unroll
-            for (int t = 0; t < TNE; t++)
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const float4 got = *reinterpret_cast<const float4 *>(take_p + ((tm * TNE + t) * 4 + q) * 256);
-                    acc[tm][t][4 * q + 0] += got.x;
-                    acc[tm][t][4 * q + 1] += got.y;
-                    acc[tm][t][4 * q + 2] += got.z;
-                    acc[tm][t][4 * q + 3] += got.w;
-                }
-    }
+    uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
     if (!producer)
 #pragma unroll
     for (int tm = 0; tm < TM; tm++) {
@@ -634,14 +583,14 @@ void conv_kernel(ConvParams p)
             const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
             const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
 #pragma unroll
-            for (int tn = 0; tn < TNE; tn++) {
+            for (int tn = 0; tn < TN; tn++) {
                 float r[4];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     float v = acc[tm][tn][4 * q + e] + bv[e];
                     r[e] = v < relu_floor ? 0.f : v;      // ReLU when relu_floor = 0, identity when -inf; NaN passes through
                 }
-                const int pl = (wn * TN + kg * TNE + tn) * 32 + (lane & 31);
+                const int pl = (wn * TN + tn) * 32 + (lane & 31);
                 *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
             }
         }
@@ -670,12 +619,11 @@ void conv_kernel(ConvParams p)
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false, int KSPLIT = 1, bool SPEC = false>
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false, bool SPEC = false>
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW, DEEP, KSPLIT>();
-    if (MODE == MODE_TAPS && p0.Cin % (32 * KSPLIT) != 0) return SS_ERR_INVALID_ARG;   // a chunk is 32*KSPLIT whole channels
+    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW, DEEP>();
     static_assert(smem <= 160 * 1024, "LDS tile too large");
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
@@ -683,7 +631,7 @@ static int launch(const ConvParams &p0, hipStream_t s)
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
-    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, KSPLIT, SPEC>;
+    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, SPEC>;
     if (smem > 64 * 1024) {
         static bool attr_set = false;    // once per process: raises this kernel's dynamic-LDS limit
         if (!attr_set) {
@@ -693,7 +641,7 @@ static int launch(const ConvParams &p0, hipStream_t s)
             attr_set = true;
         }
     }
-    kern<<<dim3((unsigned)blocks), dim3((WAVES_M * WAVES_N * KSPLIT + (SPEC ? 4 : 0)) * 64), smem, s>>>(p);
+    kern<<<dim3((unsigned)blocks), dim3((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64), smem, s>>>(p);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
 }
 
@@ -702,18 +650,17 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
     return (long long)((p.Cout + bm - 1) / bm) * (((long long)p.P + bn - 1) / bn);
 }
 
-// Tile shapes (WAVES_M x WAVES_N waves, each TM x TN tiles of 32x32; "deep" = DEEP prefetch):
-//   id 0:  64 x  64 (2x2 waves, 1x1)       id 1: same, deep
-//   id 2: 128 x  64 (4x1 waves, 1x2)       id 3: same, deep
-//   id 4: 256 x  64 (4x1 waves, 2x2)       id 5: same, deep
-//   id 6: as 3, id 7: as 5, with two wave groups (8 waves) that split the reduction of the tile
-//   id 8: as 3, id 9: as 5, plus four producer waves that build the activation chunks
-//   id 10: 128 x 64 as 2x1 waves of 2x2 tiles in two reduction groups, plus producer waves: half the LDS reads
-//          of id 8 (a wave's activation fragments serve two row tiles) for the same weight traffic
-//   id 11: 128 x 64 as 2x1 waves of 2x2 tiles plus producer waves: the same saving with two multiplying waves
-// Layouts with all four waves along the output channels fetch no weight tile twice inside a
-// workgroup; 2x2 layouts of the same tile sizes, 8-wave workgroups, 128x128 and 256x128 tiles were
-// measured and lost everywhere, so they are not instantiated.
+// Tile shapes (WAVES_M x WAVES_N multiplying waves, each TM x TN tiles of 32x32):
+//   id 0:  64 x  64 (2x2 waves, 1x1)
+//   id 1:  same, deep prefetch
+//   id 2: 128 x  64 (4x1 waves, 1x2)
+//   id 3: 256 x  64 (4x1 waves, 2x2), deep prefetch
+//   id 4: 128 x  64 (4x1 waves, 1x2), deep prefetch, plus four producer waves
+//   id 5: 256 x  64 (4x1 waves, 2x2), deep prefetch, plus four producer waves
+// Layouts with all four waves along the output channels fetch no weight tile twice inside a workgroup.
+// Measured and dropped because they won nowhere: 2x2 layouts of the larger tiles, 128x128 and 256x128 tiles,
+// deep 128x64 and shallow 256x64 without producer waves, and splitting a tile's reduction over two wave groups
+// (halves the LDS reads per multiply, but the exchange of partial sums and the doubled first chunk cost more).
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int launch_tile(int id, const ConvParams &p, hipStream_t s)
 {
@@ -721,15 +668,9 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
         case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, false>(p, s);
         case 1: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, true>(p, s);
         case 2: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, false>(p, s);
-        case 3: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true>(p, s);
-        case 4: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, false>(p, s);
-        case 5: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true>(p, s);
-        case 6: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, 2>(p, s);
-        case 7: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, 2>(p, s);
-        case 8: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, 1, true>(p, s);
-        case 9: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, 1, true>(p, s);
-        case 10: return launch<DT, SPARSE, 2, 1, 2, 2, MODE, KH, KW, true, 2, true>(p, s);
-        case 11: return launch<DT, SPARSE, 2, 1, 2, 2, MODE, KH, KW, true, 1, true>(p, s);
+        case 3: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true>(p, s);
+        case 4: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, true>(p, s);
+        case 5: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, true>(p, s);
         default: break;
     }
     return SS_ERR_INVALID_ARG;
@@ -738,23 +679,27 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
-    constexpr bool wide_ok = !(MODE == MODE_TAPS && KH * KW > 4);   // 3x3: the unfolded chunk is large, prefer 64-pixel tiles
     const char *env = getenv("SS_TILE");               // tuning aid: force a tile shape by id
     const int forced = env ? atoi(env) : -1;
     if (forced >= 0) {
         int st = launch_tile<DT, SPARSE, MODE, KH, KW>(forced, p, s);
         if (st != SS_ERR_INVALID_ARG) return st;
     }
-    // Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes).  Deep prefetch pays when
-    // few workgroups share a compute unit (small grids) and for the 3x3 transpose path.
+    // Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes, 256 compute units).
     constexpr bool pointwise = MODE == MODE_PW || MODE == MODE_PW2;
+    constexpr bool taps3x3 = MODE == MODE_TAPS && KH * KW > 4;
     if (p.Cout <= 64) {
         const bool deep = n_blocks(p, 64, 64) <= 1024 || (pointwise && p.K >= 256);
         return launch_tile<DT, SPARSE, MODE, KH, KW>(deep ? 1 : 0, p, s);
     }
-    if (!wide_ok) return launch_tile<DT, SPARSE, MODE, KH, KW>(3, p, s);
-    if (p.Cout >= 512 && p.K >= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
-    return launch_tile<DT, SPARSE, MODE, KH, KW>(n_blocks(p, 128, 64) <= 1024 ? 3 : 2, p, s);
+    // Grids of at most one workgroup per compute unit: nothing else hides a wave's stalls, so separate producer
+    // waves pay.  Larger grids do better with two four-wave workgroups per compute unit.
+    const long long b128 = n_blocks(p, 128, 64), b256 = n_blocks(p, 256, 64);
+    if (p.Cout > 128 && b256 > 128 && b256 <= 256) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
+    if (b128 <= 256) return launch_tile<DT, SPARSE, MODE, KH, KW>(4, p, s);
+    if (p.Cout >= 512 && p.K >= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(3, p, s);
+    if (taps3x3 && p.Cout >= 256 && b256 >= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(3, p, s);
+    return launch_tile<DT, SPARSE, MODE, KH, KW>(2, p, s);
 }
 
 template <int DT, bool SPARSE>

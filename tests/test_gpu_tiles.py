@@ -15,7 +15,7 @@ from helpers import check_close, oracle_ref, run_gpu
 
 pytestmark = pytest.mark.gpu
 
-TILE_IDS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]
+TILE_IDS = [0, 1, 2, 3, 4, 5]
 
 
 def _L(N, H, W, cin, cout, k, s=1, p=0, dtype=wl.F16, korder=wl.K_CRS, seed=0):
@@ -31,7 +31,7 @@ SHAPES = [
     _L(2, 12, 12, 96, 200, 2, s=2),                        # 2x2 stride 2 tap transpose
     _L(2, 9, 9, 24, 140, 3, p=1, korder=wl.K_RSC),         # channels-last flattening with taps
     _L(1, 11, 9, 12, 150, 3, p=1),                         # gather fallback (cin % 32 != 0)
-    _L(2, 14, 14, 192, 260, 3, p=1, seed=3),               # 64-channel chunks for the split-reduction tiles (3 chunks)
+    _L(2, 14, 14, 192, 260, 3, p=1, seed=3),               # six chunks of 32 channels
 ]
 
 
