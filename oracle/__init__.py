@@ -23,7 +23,7 @@ _LIB = _HERE / "libss_oracle.so"
 
 F16, BF16 = 0, 1
 K_CRS, K_RSC = 0, 1
-ACT_NONE, ACT_RELU = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
 
 def build(force: bool = False) -> Path:
@@ -57,11 +57,11 @@ def _load():
         lib.ss_oracle_decompress.argtypes = [p, p, i64, i64, p]
         lib.ss_oracle_conv2d.restype = ctypes.c_int
         lib.ss_oracle_conv2d.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
-                                         ctypes.c_int, ctypes.c_int, p, i64, i64, i64, i64,
+                                         ctypes.c_int, ctypes.c_int, p, p, i64, i64, i64, i64,
                                          ctypes.c_int, p]
         lib.ss_oracle_conv2d_points.restype = ctypes.c_int
         lib.ss_oracle_conv2d_points.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
-                                                ctypes.c_int, ctypes.c_int, p, i64, i64, i64, i64,
+                                                ctypes.c_int, ctypes.c_int, p, p, i64, i64, i64, i64,
                                                 ctypes.c_int, p, i64, p]
         _lib = lib
     return _lib
@@ -129,8 +129,9 @@ def _out_hw(H, Wd, kh, kw, stride, pad):
 
 
 def conv2d(x_bits, W_bits, M, *, cin, kh, kw, korder=K_CRS, dtype=F16, bias=None,
-           stride=(1, 1), pad=(0, 0), act=ACT_NONE) -> np.ndarray:
-    """Masked convolution, fp64, NHWC in / NHWC out, not rounded.  M=None: plain dense conv."""
+           stride=(1, 1), pad=(0, 0), act=ACT_NONE, residual=None) -> np.ndarray:
+    """Masked convolution, fp64, NHWC in / NHWC out, not rounded.  M=None: plain dense conv.
+    residual: 16-bit patterns [N, Ho, Wo, cout] added before the activation."""
     x_bits, W_bits = _c(x_bits, np.uint16), _c(W_bits, np.uint16)
     N, H, Wd, c = x_bits.shape
     assert c == cin
@@ -145,17 +146,20 @@ def conv2d(x_bits, W_bits, M, *, cin, kh, kw, korder=K_CRS, dtype=F16, bias=None
     Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
     if Ho <= 0 or Wo <= 0:
         raise ValueError("empty output")
+    if residual is not None:
+        residual = _c(residual, np.uint16)
+        assert residual.shape == (N, Ho, Wo, cout)
     y = np.empty((N, Ho, Wo, cout), dtype=np.float64)
     st = _load().ss_oracle_conv2d(_ptr(x_bits), N, H, Wd, cin, _ptr(W_bits), _ptr(M), cout, kh, kw,
-                                  korder, dtype, _ptr(bias), stride[0], stride[1], pad[0], pad[1],
-                                  act, _ptr(y))
+                                  korder, dtype, _ptr(bias), _ptr(residual), stride[0], stride[1],
+                                  pad[0], pad[1], act, _ptr(y))
     if st:
         raise ValueError(f"oracle conv2d failed (status {st})")
     return y
 
 
 def conv2d_points(x_bits, W_bits, M, flat_idx, *, cin, kh, kw, korder=K_CRS, dtype=F16, bias=None,
-                  stride=(1, 1), pad=(0, 0), act=ACT_NONE) -> np.ndarray:
+                  stride=(1, 1), pad=(0, 0), act=ACT_NONE, residual=None) -> np.ndarray:
     """The same definition at sampled flat NHWC output indices only."""
     x_bits, W_bits = _c(x_bits, np.uint16), _c(W_bits, np.uint16)
     N, H, Wd, c = x_bits.shape
@@ -168,10 +172,14 @@ def conv2d_points(x_bits, W_bits, M, flat_idx, *, cin, kh, kw, korder=K_CRS, dty
     flat_idx = _c(flat_idx, np.int64)
     Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
     assert flat_idx.min() >= 0 and flat_idx.max() < N * Ho * Wo * cout
+    if residual is not None:
+        residual = _c(residual, np.uint16)
+        assert residual.shape == (N, Ho, Wo, cout)
     out = np.empty(flat_idx.shape, dtype=np.float64)
     st = _load().ss_oracle_conv2d_points(_ptr(x_bits), N, H, Wd, cin, _ptr(W_bits), _ptr(M), cout,
-                                         kh, kw, korder, dtype, _ptr(bias), stride[0], stride[1],
-                                         pad[0], pad[1], act, _ptr(flat_idx), flat_idx.size, _ptr(out))
+                                         kh, kw, korder, dtype, _ptr(bias), _ptr(residual), stride[0],
+                                         stride[1], pad[0], pad[1], act, _ptr(flat_idx), flat_idx.size,
+                                         _ptr(out))
     if st:
         raise ValueError(f"oracle conv2d_points failed (status {st})")
     return out

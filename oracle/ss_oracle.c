@@ -19,6 +19,11 @@
  * Arithmetic: inputs are the exact values of their fp16 / bf16 bit patterns; every product and
  * the running sum are fp64; the bias is fp32 widened to fp64; the result is NOT rounded.
  *
+ * Tail of a layer (the paper's layer model sigma(Wx + b), Lemma 3.1, inside a residual block):
+ * z = conv + bias + residual (the residual is a 16-bit NHWC tensor of the output's shape, taken
+ * at its exact value), then act(z): identity, ReLU max(z, 0), or GELU z * Phi(z) with the exact
+ * standard normal CDF Phi(z) = (1 + erf(z / sqrt 2)) / 2.
+ *
  * Weight matrices are [cout][K] with K = cin*kh*kw and one of two flattenings of (c, r, t):
  *   korder 0 ("CRS", the paper's: channel slowest, kernel column fastest)  k = (c*kh + r)*kw + t
  *   korder 1 ("RSC", channels-last flattening)                             k = (r*kw + t)*cin + c
@@ -26,7 +31,9 @@
  *
  * Parity pins (tests, CPU only): unfold+matmul (Eq. 5) in numpy, a float64 library conv,
  * one-hot-kernel shifts, all-ones closed forms, linearity, 1x1 == matmul, brute-force over the
- * six patterns, round trip, byte count 9/16.  No function here is "parity unpinned".
+ * six patterns, round trip, byte count 9/16; the tail by W = 0 closed forms, the identity
+ * gelu(z) - gelu(-z) = z, tabulated values of Phi, and a library normal CDF.  No function here
+ * is "parity unpinned".
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -142,6 +149,14 @@ static int64_t kflat(int korder, int64_t c, int64_t r, int64_t t, int64_t cin, i
     return korder == 0 ? (c * kh + r) * kw + t : (r * kw + t) * cin + c;
 }
 
+/* act: 0 identity, 1 ReLU (a NaN stays a NaN), 2 GELU with the exact normal CDF. */
+static double layer_tail(double z, int act)
+{
+    if (act == 1) return (z > 0.0 || z != z) ? z : 0.0;
+    if (act == 2) return z * 0.5 * (1.0 + erf(z / sqrt(2.0)));
+    return z;
+}
+
 /* Eq. (4) with H <- M (.) W (Eq. 6), for cout kernels, a batch of N inputs, strides and
  * symmetric zero padding; bias and activation follow the layer model sigma(Wx + b) of
  * Lemma 3.1 with sigma in {identity (act=0), ReLU (act=1)}.
@@ -149,11 +164,12 @@ static int64_t kflat(int korder, int64_t c, int64_t r, int64_t t, int64_t cin, i
  *   W    [cout][K]           16-bit patterns, flattening per korder
  *   M    [cout][K]           0/1 bytes; NULL means all ones (plain dense convolution)
  *   bias [cout] fp32 or NULL
+ *   residual [N][Ho][Wo][cout] 16-bit patterns of `dtype`, or NULL: added before the activation
  *   y    [N][Ho][Wo][cout]   fp64, not rounded
  * Returns 0, or 3 if the output would be empty. */
 int ss_oracle_conv2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin,
                      const uint16_t *W, const uint8_t *M, int64_t cout, int64_t kh, int64_t kw,
-                     int korder, int dtype, const float *bias,
+                     int korder, int dtype, const float *bias, const uint16_t *residual,
                      int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, int act,
                      double *y)
 {
@@ -189,8 +205,9 @@ int ss_oracle_conv2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_
                         }
                     }
                     if (bias) acc += (double)bias[o];
-                    if (act == 1 && !(acc > 0.0)) acc = (acc != acc) ? acc : 0.0;
-                    y[((n * Ho + ho) * Wo + wo) * cout + o] = acc;
+                    int64_t yi = ((n * Ho + ho) * Wo + wo) * cout + o;
+                    if (residual) acc += ss_oracle_bits_to_double(residual[yi], dtype);
+                    y[yi] = layer_tail(acc, act);
                 }
             }
         }
@@ -205,7 +222,7 @@ int ss_oracle_conv2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_
  * take the CPU too long. */
 int ss_oracle_conv2d_points(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin,
                             const uint16_t *W, const uint8_t *M, int64_t cout, int64_t kh, int64_t kw,
-                            int korder, int dtype, const float *bias,
+                            int korder, int dtype, const float *bias, const uint16_t *residual,
                             int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, int act,
                             const int64_t *flat_idx, int64_t npts, double *out)
 {
@@ -213,9 +230,11 @@ int ss_oracle_conv2d_points(const uint16_t *x, int64_t N, int64_t H, int64_t Wd,
     int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
     if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
     int64_t K = cin * kh * kw;
+    (void)N;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < npts; i++) {
         int64_t f = flat_idx[i];
+        const int64_t yi = f;
         int64_t o = f % cout; f /= cout;
         int64_t wo = f % Wo; f /= Wo;
         int64_t ho = f % Ho; f /= Ho;
@@ -235,8 +254,8 @@ int ss_oracle_conv2d_points(const uint16_t *x, int64_t N, int64_t H, int64_t Wd,
                 }
             }
         if (bias) acc += (double)bias[o];
-        if (act == 1 && !(acc > 0.0)) acc = (acc != acc) ? acc : 0.0;
-        out[i] = acc;
+        if (residual) acc += ss_oracle_bits_to_double(residual[yi], dtype);
+        out[i] = layer_tail(acc, act);
     }
     return 0;
 }

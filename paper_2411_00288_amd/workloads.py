@@ -21,7 +21,7 @@ import numpy as np
 
 F16, BF16 = 0, 1
 K_CRS, K_RSC = 0, 1
-ACT_NONE, ACT_RELU = 0, 1
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
 # The six 2-of-4 patterns in lexicographic order of the kept positions (pattern matrix D of Eq. 2).
 PATTERNS = np.array([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1],
