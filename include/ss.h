@@ -57,7 +57,7 @@ enum {
 
 enum { SS_F16 = 0, SS_BF16 = 1 };
 enum { SS_K_CRS = 0, SS_K_RSC = 1 };
-enum { SS_ACT_NONE = 0, SS_ACT_RELU = 1 };
+enum { SS_ACT_NONE = 0, SS_ACT_RELU = 1, SS_ACT_GELU = 2 };
 
 /* Describes one weight matrix W in R^{cout x (cin*kh*kw)} (Eq. 5).  Plain data, passed by pointer [host]. */
 typedef struct {
@@ -144,7 +144,7 @@ int ss_conv2d_workspace_bytes(const ss_weight_desc *desc, int32_t N, int32_t H, 
  *   x         [N][H][Wd][cin]    16-bit, desc->dtype                        (read only)
  *   packed    buffer written by ss_mask_compress for the same desc          (read only)
  *   bias      [cout] fp32, or NULL for no bias                              (read only)
- *   act       SS_ACT_NONE | SS_ACT_RELU
+ *   act       SS_ACT_NONE | SS_ACT_RELU | SS_ACT_GELU (z * Phi(z), exact normal CDF)
  *   y         [N][Ho][Wo][cout]  16-bit, desc->dtype                        (written)
  *   workspace ws_bytes >= ss_conv2d_workspace_bytes(...) bytes, 256-byte aligned; may be NULL
  *             when that size is 0.  Contents are scratch.
@@ -164,6 +164,28 @@ int ss_conv2d_dense_fwd(const ss_weight_desc *desc, const void *x, int32_t N, in
                         const void *dense, const float *bias,
                         int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
                         void *y, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * The masked convolution as the last layer of a residual block: the layer model sigma(Wx + b) of
+ * Lemma 3.1 with the block's skip connection added before the activation,
+ *     y = act( conv(x) + bias + residual ),
+ * computed in fp32 and rounded once at the store.  Saves the separate pass that would read and
+ * rewrite the whole activation tensor.
+ *   residual  [N][Ho][Wo][cout]  16-bit, desc->dtype, 16-byte aligned, or NULL (then the call is
+ *             ss_conv2d_fwd).  Read only; it may be the same buffer as y (every element is read
+ *             by the thread that then writes it).
+ * Every other argument, and the error behaviour, as for ss_conv2d_fwd.
+ */
+int ss_conv2d_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                      const void *packed, const float *bias, const void *residual,
+                      int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
+                      void *y, void *workspace, size_t ws_bytes, void *stream);
+
+/* The dense twin of ss_conv2d_res_fwd (operand built by ss_dense_pack). */
+int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                            const void *dense, const float *bias, const void *residual,
+                            int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
+                            void *y, void *workspace, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

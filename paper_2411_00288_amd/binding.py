@@ -18,10 +18,11 @@ SS_OK = 0
 SS_ERR_INVALID_ARG, SS_ERR_BAD_MASK, SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP = -1, -2, -3, -4, -5
 SS_F16, SS_BF16 = 0, 1
 SS_K_CRS, SS_K_RSC = 0, 1
-SS_ACT_NONE, SS_ACT_RELU = 0, 1
+SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
-           "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd"]
+           "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
+           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd"]
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -55,6 +56,9 @@ def _load() -> ctypes.CDLL:
     conv_args = [dp, vp, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ss_conv2d_fwd.argtypes = conv_args
     lib.ss_conv2d_dense_fwd.argtypes = conv_args
+    res_args = conv_args[:7] + [vp] + conv_args[7:]          # residual after bias
+    lib.ss_conv2d_res_fwd.argtypes = res_args
+    lib.ss_conv2d_dense_res_fwd.argtypes = res_args
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -177,7 +181,7 @@ def out_shape(desc, N, H, W, stride=(1, 1), pad=(0, 0)):
     return (N, Ho, Wo, desc.cout)
 
 
-def _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream):
+def _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream, residual=None, with_res=False):
     if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
     N, H, W, _ = x.shape
@@ -193,14 +197,18 @@ def _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream
     if need > 0 and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         ws_bytes = need
-    args = (ctypes.byref(desc), _dev_ptr(x, "x", (torch_dtype(desc.dtype),)), N, H, W, _dev_ptr(wbuf, "weights"),
-            _dev_ptr(bias, "bias", (torch.float32,), allow_none=True), stride[0], stride[1], pad[0], pad[1], act,
+    if residual is not None and (tuple(residual.shape) != shp or residual.dtype != x.dtype or not residual.is_contiguous()):
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: residual must be contiguous {shp} {x.dtype}")
+    head = (ctypes.byref(desc), _dev_ptr(x, "x", (torch_dtype(desc.dtype),)), N, H, W, _dev_ptr(wbuf, "weights"),
+            _dev_ptr(bias, "bias", (torch.float32,), allow_none=True))
+    tail = (stride[0], stride[1], pad[0], pad[1], act,
             _dev_ptr(y, "y"), _dev_ptr(workspace, "workspace", allow_none=True), ws_bytes)
+    args = head + ((_dev_ptr(residual, "residual", allow_none=True),) if with_res else ()) + tail
     return args, y, workspace
 
 
-def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream):
-    args, y, _ws = _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream)
+def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream, residual=None, with_res=False):
+    args, y, _ws = _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream, residual, with_res)
     st = fn(*args, _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, what)
@@ -208,15 +216,18 @@ def _conv(fn, what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream)
 
 
 def prepare_conv2d(desc, x, wbuf, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None, workspace=None,
-                   sparse=True):
-    """Marshal the arguments of ss_conv2d_fwd / ss_conv2d_dense_fwd once and return (launch, y):
+                   sparse=True, residual=None):
+    """Marshal the arguments of ss_conv2d_fwd / ss_conv2d_dense_fwd (ss_conv2d_res_fwd / ss_conv2d_dense_res_fwd
+    when a residual is given) once and return (launch, y):
     ``launch()`` enqueues the call on the current torch stream.  For launch-bound loops and graph
     capture, where per-call Python argument checking would dominate.  The tensors passed here
     must stay alive and in place for as long as ``launch`` is used."""
-    fn = _lib.ss_conv2d_fwd if sparse else _lib.ss_conv2d_dense_fwd
-    what = "ss_conv2d_fwd" if sparse else "ss_conv2d_dense_fwd"
-    args, y, ws = _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, None)
-    keep = (desc, x, wbuf, bias, y, ws)
+    with_res = residual is not None
+    what = ("ss_conv2d_res_fwd" if sparse else "ss_conv2d_dense_res_fwd") if with_res else \
+           ("ss_conv2d_fwd" if sparse else "ss_conv2d_dense_fwd")
+    fn = getattr(_lib, what)
+    args, y, ws = _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, None, residual, with_res)
+    keep = (desc, x, wbuf, bias, y, ws, residual)
 
     def launch(_keep=keep):
         st = fn(*args, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
@@ -236,3 +247,17 @@ def ss_conv2d_dense_fwd(desc, x, dense, bias=None, stride=(1, 1), pad=(0, 0), ac
     """The dense-MFMA twin on the operand built by ss_dense_pack."""
     return _conv(_lib.ss_conv2d_dense_fwd, "ss_conv2d_dense_fwd", desc, x, dense, bias, stride, pad, act, y,
                  workspace, stream)
+
+
+def ss_conv2d_res_fwd(desc, x, packed, bias=None, residual=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
+                      workspace=None, stream=None) -> torch.Tensor:
+    """2:4-sparse convolution closing a residual block: y = act(conv(x) + bias + residual), residual NHWC like y."""
+    return _conv(_lib.ss_conv2d_res_fwd, "ss_conv2d_res_fwd", desc, x, packed, bias, stride, pad, act, y, workspace,
+                 stream, residual, True)
+
+
+def ss_conv2d_dense_res_fwd(desc, x, dense, bias=None, residual=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE,
+                            y=None, workspace=None, stream=None) -> torch.Tensor:
+    """The dense-MFMA twin of ss_conv2d_res_fwd."""
+    return _conv(_lib.ss_conv2d_dense_res_fwd, "ss_conv2d_dense_res_fwd", desc, x, dense, bias, stride, pad, act, y,
+                 workspace, stream, residual, True)

@@ -39,6 +39,7 @@ struct ConvParams {
     const uint8_t *a_vals;    // first value tile (after the header)
     const uint32_t *a_meta;   // first metadata tile (sparse only)
     const float *bias;
+    const uint16_t *residual; // [P][Cout] like y, or nullptr
     uint16_t *y;
     int N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, Ho, Wo, P, K, Ks, Kp, Mt, act, korder;
     int tiles_m;
@@ -96,6 +97,16 @@ __device__ __forceinline__ uint32_t cvt_pack2(float a, float b)
     }
 }
 
+// Exact value of a 16-bit pattern as fp32.
+template <int DT>
+__device__ __forceinline__ float widen(uint16_t bits)
+{
+    if constexpr (DT == SS_F16)
+        return (float)__builtin_bit_cast(_Float16, bits);
+    else
+        return __builtin_bit_cast(float, (uint32_t)bits << 16);
+}
+
 // How the [pixels x reduction-chunk] slice of the unfolded input is built in LDS:
 //   MODE_VEC    channels are contiguous inside every aligned run of 8 reduction indices (1x1
 //               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads,
@@ -144,13 +155,20 @@ constexpr int ring_size(int ksteps, int regs_per_step, int budget)
         if (ksteps % r == 0 || r % ksteps == 0) return r;
 }
 
+// LDS of a workgroup: the staging buffers, reused by the epilogue for the output tile (16-bit, or fp32 when a
+// residual is added after it), followed by the tile's bias values (fp32).
 template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
-constexpr size_t smem_bytes()
+constexpr size_t smem_body(bool with_residual)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
     size_t stage = (size_t)CS::NBUF * BN * CS::ROW * 2;
-    size_t epi = (size_t)BN * (BM * 2 + 8);
-    return (stage > epi ? stage : epi) + (size_t)BM * 4;      // + the tile's bias values (fp32)
+    size_t epi = with_residual ? (size_t)BN * (BM + 4) * 4 : (size_t)BN * (BM * 2 + 8);
+    return stage > epi ? stage : epi;
+}
+template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
+constexpr size_t smem_bytes(bool with_residual)
+{
+    return smem_body<BM, BN, MODE, KH, KW, DEEP>(with_residual) + (size_t)BM * 4;
 }
 
 // Waves per SIMD the register allocator must leave room for: small wave tiles are latency-bound
@@ -169,7 +187,7 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // wave's matrix instructions.
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC>
 __global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
-__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == 2 && KH * KW > 4))))
+__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS))))
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
@@ -218,7 +236,9 @@ void conv_kernel(ConvParams p)
 
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
-    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (smem_bytes<BM, BN, MODE, KH, KW, DEEP>() - (size_t)BM * 4));
+    const bool with_res = p.residual != nullptr;     // uniform
+    float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) +
+                                              (with_res ? smem_body<BM, BN, MODE, KH, KW, DEEP>(true) : smem_body<BM, BN, MODE, KH, KW, DEEP>(false)));
     // (Loaded after the first activation / weight loads are on their way: issued first, its latency would
     // sit in front of everything else.)
     float bias_r[(BM + NMATH - 1) / NMATH];
@@ -569,50 +589,127 @@ void conv_kernel(ConvParams p)
     }   // !producer
 
     // ------------------------------------------------------------------ epilogue
-    // bias + activation in fp32, one rounding to the 16-bit type, then through LDS so that every
-    // pixel's run of BM output channels leaves as 16-byte, fully coalesced NHWC stores.
-    const float relu_floor = p.act == SS_ACT_RELU ? 0.f : -__builtin_inff();
-    constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
-    uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
-    if (!producer)
-#pragma unroll
-    for (int tm = 0; tm < TM; tm++) {
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const int ol = (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);    // first of 4 consecutive output channels (tile-local)
-            const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
-            const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
-#pragma unroll
-            for (int tn = 0; tn < TN; tn++) {
-                float r[4];
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    float v = acc[tm][tn][4 * q + e] + bv[e];
-                    r[e] = v < relu_floor ? 0.f : v;      // ReLU when relu_floor = 0, identity when -inf; NaN passes through
-                }
-                const int pl = (wn * TN + tn) * 32 + (lane & 31);
-                *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
-            }
-        }
-    }
-    __syncthreads();
+    // bias (+ residual) + activation in fp32, one rounding to the 16-bit type; the tile goes through LDS so that
+    // every pixel's run of BM output channels leaves as 16-byte, fully coalesced NHWC stores.
     constexpr int RUNS = BM / 8;                  // 16-byte runs per pixel row
     const bool vec_ok = (p.Cout & 7) == 0;
-    for (int it = tid; it < BN * RUNS; it += NT) {
-        const int pl = it / RUNS, run = it % RUNS;
-        const int pg = n0 + pl, o = m0 + run * 8;
-        if (pg >= p.P || o >= p.Cout) continue;
-        const uint2 lo = *reinterpret_cast<const uint2 *>(Cs + pl * CROW + run * 8);
-        const uint2 hi = *reinterpret_cast<const uint2 *>(Cs + pl * CROW + run * 8 + 4);
-        uint16_t *dst = p.y + (size_t)pg * p.Cout + o;
-        if (vec_ok) {
-            *reinterpret_cast<uint4 *>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        } else {
-            const uint32_t w[4] = {lo.x, lo.y, hi.x, hi.y};
+    // The thread index again, from the wave number (scalar) and the lane count: keeping the launch-time register
+    // alive across the main loop costs a spill in the variants that run at the register limit.
+    const int etid = wave * 64 + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const float relu_floor = p.act == SS_ACT_RELU ? 0.f : -__builtin_inff();
+    // ReLU when relu_floor = 0, identity when -inf (a NaN passes through); GELU = z * Phi(z) with the exact normal
+    // CDF, written with erfc so that the lower tail keeps its relative accuracy
+    auto relu_or_id = [&](float v) { return v < relu_floor ? 0.f : v; };
+    auto gelu = [](float v) { return 0.5f * v * erfcf(-0.70710678118654752f * v); };
+    if (!with_res) {
+        constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
+        uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
+        auto to_lds = [&](auto actf) {
 #pragma unroll
-            for (int e = 0; e < 8; e++)
-                if (o + e < p.Cout) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            for (int tm = 0; tm < TM; tm++) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const int ol = (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);    // first of 4 consecutive output channels (tile-local)
+                    const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
+                    const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++) {
+                        float r[4];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) r[e] = actf(acc[tm][tn][4 * q + e] + bv[e]);
+                        const int pl = (wn * TN + tn) * 32 + (lane & 31);
+                        *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
+                    }
+                }
+            }
+        };
+        if (!producer) {
+            if (p.act == SS_ACT_GELU) to_lds(gelu); else to_lds(relu_or_id);
         }
+        __syncthreads();
+        for (int it = etid; it < BN * RUNS; it += NT) {
+            const int pl = it / RUNS, run = it % RUNS;
+            const int pg = n0 + pl, o = m0 + run * 8;
+            if (pg >= p.P || o >= p.Cout) continue;
+            const uint2 lo = *reinterpret_cast<const uint2 *>(Cs + pl * CROW + run * 8);
+            const uint2 hi = *reinterpret_cast<const uint2 *>(Cs + pl * CROW + run * 8 + 4);
+            uint16_t *dst = p.y + (size_t)pg * p.Cout + o;
+            if (vec_ok) {
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            } else {
+                const uint32_t w[4] = {lo.x, lo.y, hi.x, hi.y};
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    if (o + e < p.Cout) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+    } else {
+        // With a residual the tile crosses LDS in fp32 (conv + bias); the thread that stores a 16-byte run adds the
+        // residual's run (fetched before the tile is written, so its latency hides behind the LDS phase), applies
+        // the activation and rounds once.
+        constexpr int CROW = BM + 4;     // floats per pixel row (+16 bytes: 16-byte writes of consecutive pixels spread over the banks)
+        constexpr int ITERS = (BN * RUNS + NT - 1) / NT;
+        float *Cf = reinterpret_cast<float *>(smem);
+        u32x4 res[ITERS];
+        auto load_res = [&]() {
+            if (!vec_ok) return;
+#pragma unroll
+            for (int j = 0; j < ITERS; j++) {
+                const int it = etid + j * NT;
+                const int pl = it / RUNS, run = it % RUNS;
+                const int pg = n0 + pl, o = m0 + run * 8;
+                res[j] = u32x4{0u, 0u, 0u, 0u};
+                if (it < BN * RUNS && pg < p.P && o < p.Cout)
+                    res[j] = *reinterpret_cast<const u32x4 *>(p.residual + (size_t)pg * p.Cout + o);
+            }
+        };
+        if constexpr (DEEP) load_res();      // (the shallow variants have no registers to spare next to the accumulators)
+        if (!producer) {
+#pragma unroll
+            for (int tm = 0; tm < TM; tm++) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const int ol = (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);
+                    const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++) {
+                        const int pl = (wn * TN + tn) * 32 + (lane & 31);
+                        *reinterpret_cast<float4 *>(Cf + pl * CROW + ol) =
+                            make_float4(acc[tm][tn][4 * q + 0] + bq.x, acc[tm][tn][4 * q + 1] + bq.y,
+                                        acc[tm][tn][4 * q + 2] + bq.z, acc[tm][tn][4 * q + 3] + bq.w);
+                    }
+                }
+            }
+        }
+        if constexpr (!DEEP) load_res();
+        __syncthreads();
+        auto from_lds = [&](auto actf) {
+#pragma unroll
+            for (int j = 0; j < ITERS; j++) {
+                const int it = etid + j * NT;
+                const int pl = it / RUNS, run = it % RUNS;
+                const int pg = n0 + pl, o = m0 + run * 8;
+                if (it >= BN * RUNS || pg >= p.P || o >= p.Cout) continue;
+                const float4 lo = *reinterpret_cast<const float4 *>(Cf + pl * CROW + run * 8);
+                const float4 hi = *reinterpret_cast<const float4 *>(Cf + pl * CROW + run * 8 + 4);
+                const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                uint16_t *dst = p.y + (size_t)pg * p.Cout + o;
+                if (vec_ok) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++)
+                        w[e] = cvt_pack2<DT>(actf(v[2 * e] + widen<DT>((uint16_t)(res[j][e] & 0xFFFFu))),
+                                             actf(v[2 * e + 1] + widen<DT>((uint16_t)(res[j][e] >> 16))));
+                    *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+                } else {
+                    const uint16_t *rs = p.residual + (size_t)pg * p.Cout + o;
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        if (o + e < p.Cout) dst[e] = (uint16_t)(cvt_pack2<DT>(actf(v[e] + widen<DT>(rs[e])), 0.f) & 0xFFFFu);
+                }
+            }
+        };
+        if (p.act == SS_ACT_GELU) from_lds(gelu); else from_lds(relu_or_id);
     }
 }
 
@@ -623,8 +720,10 @@ template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MOD
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr size_t smem = smem_bytes<BM, BN, MODE, KH, KW, DEEP>();
-    static_assert(smem <= 160 * 1024, "LDS tile too large");
+    constexpr size_t smem_plain = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(false);
+    constexpr size_t smem_res = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
+    static_assert(smem_plain <= 160 * 1024 && smem_res <= 160 * 1024, "LDS tile too large");
+    const size_t smem = p0.residual ? smem_res : smem_plain;
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
     fast_div_setup((unsigned)p.tiles_m, &p.tm_mul, &p.tm_sh);
@@ -632,11 +731,11 @@ static int launch(const ConvParams &p0, hipStream_t s)
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
     auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, SPEC>;
-    if (smem > 64 * 1024) {
+    if (smem_res > 64 * 1024) {
         static bool attr_set = false;    // once per process: raises this kernel's dynamic-LDS limit
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)smem) != hipSuccess)
+                                    (int)smem_res) != hipSuccess)
                 return SS_ERR_HIP;
             attr_set = true;
         }
@@ -719,8 +818,8 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
 
 template <bool SPARSE>
 static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd, const void *wbuf,
-                      const float *bias, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int32_t act, void *y,
-                      void *workspace, size_t ws_bytes, void *stream)
+                      const float *bias, const void *residual, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
+                      int32_t act, void *y, void *workspace, size_t ws_bytes, void *stream)
 {
     (void)workspace;
     (void)ws_bytes;
@@ -728,9 +827,11 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     if (st != SS_OK) return st;
     if (!x || !wbuf || !y) return SS_ERR_INVALID_ARG;
     if (N <= 0 || H <= 0 || Wd <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return SS_ERR_INVALID_ARG;
-    if (act != SS_ACT_NONE && act != SS_ACT_RELU) return SS_ERR_INVALID_ARG;
+    if (act != SS_ACT_NONE && act != SS_ACT_RELU && act != SS_ACT_GELU) return SS_ERR_INVALID_ARG;
     if (H + 2 * ph < desc->kh || Wd + 2 * pw < desc->kw) return SS_ERR_INVALID_ARG;
-    if (!aligned(x, 16) || !aligned(wbuf, 16) || !aligned(y, 16) || (bias && !aligned(bias, 4))) return SS_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(wbuf, 16) || !aligned(y, 16) || (bias && !aligned(bias, 4)) ||
+        (residual && !aligned(residual, 16)))
+        return SS_ERR_INVALID_ARG;
     int Ho = (H + 2 * ph - desc->kh) / sh + 1;
     int Wo = (Wd + 2 * pw - desc->kw) / sw + 1;
     if (Ho <= 0 || Wo <= 0) return SS_ERR_INVALID_ARG;
@@ -749,6 +850,7 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.a_vals = static_cast<const uint8_t *>(wbuf) + kHeaderBytes;
     p.a_meta = reinterpret_cast<const uint32_t *>(p.a_vals + (size_t)t.Mt * t.Ks * 1024);
     p.bias = bias;
+    p.residual = static_cast<const uint16_t *>(residual);
     p.y = static_cast<uint16_t *>(y);
     p.N = N; p.H = H; p.W = Wd; p.Cin = desc->cin; p.Cout = desc->cout; p.kh = desc->kh; p.kw = desc->kw;
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.Ho = Ho; p.Wo = Wo; p.P = (int)P;
@@ -783,8 +885,17 @@ extern "C" int ss_conv2d_fwd(const ss_weight_desc *desc, const void *x, int32_t 
                              const void *packed, const float *bias, int32_t stride_h, int32_t stride_w, int32_t pad_h,
                              int32_t pad_w, int32_t act, void *y, void *workspace, size_t ws_bytes, void *stream)
 {
-    return conv_entry<true>(desc, x, N, H, Wd, packed, bias, stride_h, stride_w, pad_h, pad_w, act, y, workspace,
-                            ws_bytes, stream);
+    return conv_entry<true>(desc, x, N, H, Wd, packed, bias, nullptr, stride_h, stride_w, pad_h, pad_w, act, y,
+                            workspace, ws_bytes, stream);
+}
+
+extern "C" int ss_conv2d_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                 const void *packed, const float *bias, const void *residual, int32_t stride_h,
+                                 int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act, void *y, void *workspace,
+                                 size_t ws_bytes, void *stream)
+{
+    return conv_entry<true>(desc, x, N, H, Wd, packed, bias, residual, stride_h, stride_w, pad_h, pad_w, act, y,
+                            workspace, ws_bytes, stream);
 }
 
 extern "C" int ss_conv2d_dense_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
@@ -792,6 +903,15 @@ extern "C" int ss_conv2d_dense_fwd(const ss_weight_desc *desc, const void *x, in
                                    int32_t pad_h, int32_t pad_w, int32_t act, void *y, void *workspace, size_t ws_bytes,
                                    void *stream)
 {
-    return conv_entry<false>(desc, x, N, H, Wd, dense, bias, stride_h, stride_w, pad_h, pad_w, act, y, workspace,
-                             ws_bytes, stream);
+    return conv_entry<false>(desc, x, N, H, Wd, dense, bias, nullptr, stride_h, stride_w, pad_h, pad_w, act, y,
+                             workspace, ws_bytes, stream);
+}
+
+extern "C" int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                       const void *dense, const float *bias, const void *residual, int32_t stride_h,
+                                       int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act, void *y,
+                                       void *workspace, size_t ws_bytes, void *stream)
+{
+    return conv_entry<false>(desc, x, N, H, Wd, dense, bias, residual, stride_h, stride_w, pad_h, pad_w, act, y,
+                             workspace, ws_bytes, stream);
 }
