@@ -7,7 +7,8 @@ already resident in device memory; the weight compressor is a one-off per weight
 timed separately.  The dense twin is timed the same way for the speed-up ratio, and the CPU
 oracle is timed on the host cores as a reported baseline.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table]      (--table: per-layer report)
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail]   (--table: per-layer report,
+                                                                          --tail: fused residual tail report)
 """
 from __future__ import annotations
 
@@ -192,6 +193,43 @@ def print_table(torch, ss, wl, steps, warmup, cold, only=""):
     return rows
 
 
+def print_tail_table(torch, ss, wl, steps, warmup):
+    """Fused layer tail (conv + bias + residual, activation, one rounding) against the same conv followed by a
+    separate elementwise pass over the output, on the layers that close a residual block."""
+    import dataclasses
+    res_layers = [L for L in wl.resnet50_layers() if "_c3_" in L.name]
+    cnx = {L.name: L for L in wl.convnext_t_stage1_layers()}
+    cases = [(dataclasses.replace(L, act=wl.ACT_RELU), True) for L in res_layers]
+    cases += [(dataclasses.replace(cnx["cnx_pw_96_384"], act=wl.ACT_GELU), False),       # expansion: GELU, no residual
+              (dataclasses.replace(cnx["cnx_pw_384_96"], act=wl.ACT_NONE), True)]        # projection: + block input
+    print("## fused tail: y = act(conv + bias + residual) in one kernel vs conv, then a separate add / activation pass")
+    print(f"{'layer':24s} {'act':>5s} {'res':>4s} {'conv only us':>12s} {'fused us':>9s} {'separate us':>12s} {'saved us':>9s} {'fused GB/s':>10s}")
+    names = {wl.ACT_NONE: "none", wl.ACT_RELU: "relu", wl.ACT_GELU: "gelu"}
+    for L, with_res in cases:
+        run = LayerRun(dataclasses.replace(L, act=wl.ACT_NONE), torch, ss, wl, values=False)
+        x, y = run.xs[0], run.ys[0]
+        r = torch.randn_like(y) if with_res else None
+        st, pd = (L.stride,) * 2, (L.pad,) * 2
+        fused, y2 = ss.prepare_conv2d(run.desc, x, run.packed, run.bias, st, pd, L.act, sparse=True, residual=r)
+
+        def separate():
+            run.calls_s[0]()
+            if r is not None:
+                y.add_(r)
+            if L.act == wl.ACT_RELU:
+                y.relu_()
+            elif L.act == wl.ACT_GELU:
+                y.copy_(torch.nn.functional.gelu(y))
+        t_conv = median_time(torch, run.calls_s[0], steps, warmup) * 1e3
+        t_fused = median_time(torch, fused, steps, warmup) * 1e3
+        t_sep = median_time(torch, separate, steps, warmup) * 1e3
+        nbytes = L.algorithmic_bytes(True) + (y.numel() * 2 if with_res else 0)
+        print(f"{L.name:24s} {names[L.act]:>5s} {'yes' if with_res else 'no':>4s} {t_conv:12.2f} {t_fused:9.2f} {t_sep:12.2f} "
+              f"{t_sep - t_fused:9.2f} {nbytes / t_fused / 1e3:10.0f}", flush=True)
+        del run, fused, y2, r
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,6 +238,7 @@ def main():
     ap.add_argument("--table", action="store_true", help="per-layer report for all configurations instead of the JSON line")
     ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
+    ap.add_argument("--tail", action="store_true", help="report of the fused residual / activation tail instead of the JSON line")
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
                          "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
@@ -220,6 +259,9 @@ def main():
     from paper_2411_00288_amd import workloads as wl
     torch.cuda.set_device(0)
 
+    if args.tail:
+        print_tail_table(torch, ss, wl, args.steps, args.warmup)
+        return
     if args.table:
         print_table(torch, ss, wl, args.steps, args.warmup, args.cold, args.only)
         return

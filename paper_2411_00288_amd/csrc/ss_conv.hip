@@ -107,6 +107,19 @@ __device__ __forceinline__ float widen(uint16_t bits)
         return __builtin_bit_cast(float, (uint32_t)bits << 16);
 }
 
+// Standard normal CDF Phi(v) = erfc(-v / sqrt 2) / 2 for the GELU z * Phi(z).  erfc by the rational approximation
+// 7.1.26 of Abramowitz & Stegun (erfc(x) = t (a1 + t (a2 + ... a5 t)) exp(-x^2), t = 1 / (1 + p x), x >= 0; absolute
+// error below 1.5e-7, i.e. at fp32 round-off and three orders below the 16-bit output's), which costs a third of
+// the library erfc in an epilogue that otherwise only adds and rounds.
+__device__ __forceinline__ float normal_cdf(float v)
+{
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float half_erfc = 0.5f * poly * __expf(-x * x);     // Phi(-|v|)
+    return v < 0.f ? half_erfc : 1.0f - half_erfc;            // (a NaN falls through to 1 - NaN = NaN)
+}
+
 // How the [pixels x reduction-chunk] slice of the unfolded input is built in LDS:
 //   MODE_VEC    channels are contiguous inside every aligned run of 8 reduction indices (1x1
 //               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads,
@@ -600,7 +613,7 @@ void conv_kernel(ConvParams p)
     // ReLU when relu_floor = 0, identity when -inf (a NaN passes through); GELU = z * Phi(z) with the exact normal
     // CDF, written with erfc so that the lower tail keeps its relative accuracy
     auto relu_or_id = [&](float v) { return v < relu_floor ? 0.f : v; };
-    auto gelu = [](float v) { return 0.5f * v * erfcf(-0.70710678118654752f * v); };
+    auto gelu = [](float v) { return v * normal_cdf(v); };
     if (!with_res) {
         constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
         uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)

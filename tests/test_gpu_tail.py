@@ -150,3 +150,21 @@ def test_resnet_conv3_tail_full_size_sampled(ss):
     got = y.reshape(-1)[torch.from_numpy(idx).cuda()].float().cpu().numpy().astype(np.float64)
     assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 2e-3
     assert (np.abs(got - ref) <= 1e-2 * (np.abs(ref) + 1)).all()
+
+
+def test_gelu_over_a_dense_grid_of_arguments(ss):
+    # zero weights: the pre-activation is the residual, here every fp16 value with |z| <= 16 (both signs), so the
+    # kernel's normal-CDF evaluation is compared with the oracle's erf over its whole useful range
+    pats = np.arange(0, 0x4C01, dtype=np.uint16)                     # +0 .. 16.0
+    z_bits = np.concatenate([pats, pats | 0x8000])
+    C = 64
+    n = (z_bits.size + C - 1) // C
+    z_bits = np.concatenate([z_bits, np.zeros(n * C - z_bits.size, dtype=np.uint16)]).reshape(1, n, 1, C)
+    L = wl.Layer("gelu_grid", N=1, H=n, W=1, cin=32, cout=C, kh=1, kw=1, dtype=wl.F16, act=wl.ACT_GELU, mask="logits")
+    d = wl.make_inputs(L)
+    d["W"] = np.zeros_like(d["W"])
+    d["bias"] = np.zeros_like(d["bias"])
+    ref = _ref(L, d, z_bits)
+    for sparse in (True, False):
+        got = _run(ss, L, d, z_bits, sparse=sparse).float().cpu().numpy().astype(np.float64)
+        assert (np.abs(got - ref) <= 1e-3 * np.abs(ref) + 1e-6).all()
