@@ -522,8 +522,13 @@ void conv_kernel(ConvParams p)
     }
     if (!producer) {
     if constexpr (!SPEC) stage_load(0);
+    // (Issue order pinned: the loop's waits count loads in flight, and the compiler takes the weaker of the counts
+    // that hold on entry and around the back edge; values and index words must interleave here as they do there.)
 #pragma unroll
-    for (int s = 0; s < PF; s++) load_a(a[s], s);
+    for (int s = 0; s < PF; s++) {
+        load_a(a[s], s);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     load_bias();
     if constexpr (!SPEC) stage_store(Bs0);
 #pragma unroll
