@@ -233,8 +233,8 @@ def print_tail_table(torch, ss, wl, steps, warmup):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=2000)
     ap.add_argument("--table", action="store_true", help="per-layer report for all configurations instead of the JSON line")
     ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
@@ -260,10 +260,10 @@ def main():
     torch.cuda.set_device(0)
 
     if args.tail:
-        print_tail_table(torch, ss, wl, args.steps, args.warmup)
+        print_tail_table(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50))
         return
     if args.table:
-        print_table(torch, ss, wl, args.steps, args.warmup, args.cold, args.only)
+        print_table(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50), args.cold, args.only)
         return
 
     L = wl.CONFIG1
@@ -296,7 +296,7 @@ def main():
     eager_ms = time_launches(torch, run.sparse, args.steps, 2)   # host-issued launches, for reference
 
     # ---- companions (not part of `value`)
-    t_dense = median_time(torch, run.densef, args.steps, args.warmup)
+    t_dense = median_time(torch, run.densef, args.steps, min(args.warmup, 200))
     t_sparse = median_time(torch, run.sparse, args.steps, 2)
     Lbig = wl.with_batch(L, 512)                      # same layer, 16x the batch: asymptotic utilisation
     big = LayerRun(Lbig, torch, ss, wl, values=False)
