@@ -55,6 +55,8 @@ def _load():
         lib.ss_oracle_compress.argtypes = [p, p, i64, i64, p, p]
         lib.ss_oracle_decompress.restype = None
         lib.ss_oracle_decompress.argtypes = [p, p, i64, i64, p]
+        lib.ss_oracle_update.restype = None
+        lib.ss_oracle_update.argtypes = [p, p, i64, ctypes.c_int]
         lib.ss_oracle_conv2d.restype = ctypes.c_int
         lib.ss_oracle_conv2d.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
                                          ctypes.c_int, ctypes.c_int, p, p, i64, i64, i64, i64,
@@ -122,6 +124,14 @@ def decompress(vals, meta) -> np.ndarray:
     out = np.empty((cout, K), dtype=np.uint16)
     _load().ss_oracle_decompress(_ptr(vals), _ptr(meta), cout, K, _ptr(out))
     return out
+
+
+def update(W_bits, U_bits, dtype: int) -> np.ndarray:
+    """V = round16(float(W) + float(U)) element-wise (binary32 sum, one rounding to the storage type)."""
+    W_bits, U_bits = _c(W_bits, np.uint16).copy(), _c(U_bits, np.uint16)
+    assert W_bits.shape == U_bits.shape
+    _load().ss_oracle_update(_ptr(W_bits), _ptr(U_bits), W_bits.size, dtype)
+    return W_bits
 
 
 def _out_hw(H, Wd, kh, kw, stride, pad):

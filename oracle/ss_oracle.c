@@ -33,7 +33,8 @@
  * one-hot-kernel shifts, all-ones closed forms, linearity, 1x1 == matmul, brute-force over the
  * six patterns, round trip, byte count 9/16; the tail by W = 0 closed forms, the identity
  * gelu(z) - gelu(-z) = z, tabulated values of Phi, and a library normal CDF.  No function here
- * is "parity unpinned".
+ * is "parity unpinned".  The weight update's rounding is pinned against numpy's float16 and torch's bfloat16
+ * conversions (all 65536 patterns x a spread of addends: ties, carries, subnormals, overflow).
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -65,6 +66,50 @@ double ss_oracle_bits_to_double(uint16_t bits, int dtype)
         v = ldexp((double)(frac + 1024), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
     }
     return sign ? -v : v;
+}
+
+/* Round-to-nearest-even of a float to a 16-bit pattern (dtype 0: binary16, 1: bfloat16), done on the bits so that
+ * it does not depend on the compiler's half-precision support.  A NaN maps to a quiet NaN of the same sign. */
+static uint16_t float_to_bits16(float f, int dtype)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint32_t sign = u >> 31, mag = u & 0x7fffffffu;
+    if (dtype == 1) {
+        if (mag > 0x7f800000u) return (uint16_t)((sign << 15) | 0x7fc0u);
+        uint32_t r = mag + 0x7fffu + ((mag >> 16) & 1u);           /* ties to even on the kept bit */
+        return (uint16_t)((sign << 15) | (r >> 16));
+    }
+    if (mag > 0x7f800000u) return (uint16_t)((sign << 15) | 0x7e00u);
+    if (mag >= 0x47800000u) return (uint16_t)((sign << 15) | 0x7c00u);   /* >= 65536, or infinity */
+    if (mag < 0x33000000u) return (uint16_t)(sign << 15);                  /* < 2^-25: rounds to zero */
+    int e = (int)(mag >> 23) - 127;                     /* unbiased exponent, -25 .. 15 */
+    uint32_t m = (mag & 0x7fffffu) | 0x800000u;         /* 24-bit significand with the hidden one */
+    /* binary16 keeps 10 fraction bits for e >= -14; below that the value is a multiple of 2^-24 */
+    int drop = (e >= -14) ? 13 : (13 + (-14 - e));      /* low bits of m to round away (13 .. 24) */
+    uint32_t kept = m >> drop;
+    uint32_t rem = m & ((1u << drop) - 1u), half = 1u << (drop - 1);
+    if (rem > half || (rem == half && (kept & 1u))) kept++;
+    uint32_t bits;
+    if (e >= -14)
+        bits = ((uint32_t)(e + 15) << 10) + (kept - 0x400u);   /* a carry out of the significand bumps the exponent */
+    else
+        bits = kept;                                            /* subnormal (or the smallest normal after a carry) */
+    if (bits >= 0x7c00u) bits = 0x7c00u;                        /* rounded up to infinity */
+    return (uint16_t)((sign << 15) | bits);
+}
+
+/* Weight update in the storage type (Sec. 3.2, combined effect of masking and updating: the model moves to
+ * V = W + U and keeps its mask): V[i] = round16( float(W[i]) + float(U[i]) ), the sum taken in binary32 (itself
+ * rounded to nearest even) as a framework adding two 16-bit tensors does.  In place over W. */
+void ss_oracle_update(uint16_t *W, const uint16_t *U, int64_t n, int dtype)
+{
+    for (int64_t i = 0; i < n; i++) {
+        float a = (float)ss_oracle_bits_to_double(W[i], dtype);    /* exact: every 16-bit value is a float */
+        float b = (float)ss_oracle_bits_to_double(U[i], dtype);
+        volatile float sum = a + b;                                 /* one binary32 rounding, no wider intermediate */
+        W[i] = float_to_bits16(sum, dtype);
+    }
 }
 
 int ss_oracle_num_threads(void)
