@@ -304,6 +304,8 @@ def main():
     tb_d = median_time(torch, big.densef, 20, 3, reps=3)
     del big
     tc = time_launches(torch, lambda: ss.ss_mask_compress(run.desc, run.W, run.M, packed=run.packed), 20, 3)
+    Wu, Uz = run.W.clone(), torch.zeros_like(run.W)     # a zero update: the packed weights stay what they are
+    tu = time_launches(torch, lambda: ss.ss_mask_update_compress(run.desc, Wu, Uz, run.M, packed=run.packed), 20, 3)
 
     achieved = L.dense_equiv_flop / kern_ms / 1e9
     out = {
@@ -318,7 +320,7 @@ def main():
         "scaled_batch": {"workload": "same layer at N=512", "sparse_us": tb_s * 1e3, "dense_twin_us": tb_d * 1e3,
                          "tflops": Lbig.dense_equiv_flop / tb_s / 1e9, "speedup": tb_d / tb_s,
                          "frac_sparse_peak": Lbig.dense_equiv_flop / tb_s / 1e9 / SPARSE_PEAK_TFLOPS},
-        "compress_us": tc * 1e3, "eager_launch_us": eager_ms * 1e3,
+        "compress_us": tc * 1e3, "update_compress_us": tu * 1e3, "eager_launch_us": eager_ms * 1e3,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": CFG1_TRAFFIC_BYTES,
                      "traffic_unit": "bytes per launch (algorithmic: %d)" % L.algorithmic_bytes(True),

@@ -115,6 +115,21 @@ int ss_mask_compress(const ss_weight_desc *desc, const void *W, const uint8_t *M
                      void *packed, int32_t *bad_row_group, void *stream);
 
 /*
+ * Re-packing after a weight update (Sec. 3.2, the lemma on masking an updated model: the weights
+ * move to V = W + U and the mask learned for W stays).  One pass over the weights:
+ *     V = round16( float(W) + float(U) )     element-wise, binary32 sum, one rounding to nearest even,
+ *                                            written back over W,
+ *     packed = the structured representation of M (.) V, exactly as ss_mask_compress(V, M) writes it.
+ *   W  [cout][K] 16-bit, desc->dtype, 8-byte aligned                        (read and written)
+ *   U  [cout][K] 16-bit, desc->dtype, 8-byte aligned; must not overlap W    (read only)
+ * Every other argument, the synchronisation and the error behaviour as for ss_mask_compress.  W is
+ * updated in every block, also in one whose mask is invalid.  The bit pattern of a NaN result is
+ * the hardware's.
+ */
+int ss_mask_update_compress(const ss_weight_desc *desc, void *W, const void *U, const uint8_t *M,
+                            void *packed, int32_t *bad_row_group, void *stream);
+
+/*
  * Inverse of the compressor: writes M (.) W as a plain [cout][K] matrix (desc->korder), +0 at
  * the dropped positions.  Test and debugging aid; asynchronous on `stream`.
  */

@@ -22,7 +22,7 @@ SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
-           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd"]
+           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress"]
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -50,6 +50,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_packed_bytes.argtypes = [dp, ctypes.POINTER(sz)]
     lib.ss_dense_bytes.argtypes = [dp, ctypes.POINTER(sz)]
     lib.ss_mask_compress.argtypes = [dp, vp, vp, vp, ctypes.POINTER(i32), vp]
+    lib.ss_mask_update_compress.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(i32), vp]
     lib.ss_mask_decompress.argtypes = [dp, vp, vp, vp]
     lib.ss_dense_pack.argtypes = [dp, vp, vp, vp, vp]
     lib.ss_conv2d_workspace_bytes.argtypes = [dp, i32, i32, i32, i32, i32, i32, i32, ctypes.POINTER(sz)]
@@ -132,6 +133,26 @@ def ss_mask_compress(desc: ss_weight_desc, W: torch.Tensor, M: torch.Tensor, pac
                                _dev_ptr(packed, "packed"), bad, _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_mask_compress", detail=(bad[0], bad[1]) if st == SS_ERR_BAD_MASK else None)
+    return packed
+
+
+def ss_mask_update_compress(desc: ss_weight_desc, W: torch.Tensor, U: torch.Tensor, M: torch.Tensor,
+                            packed: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """W <- round16(W + U) in place, and packed <- compress(W, M): re-packing after a weight update."""
+    K = desc.cin * desc.kh * desc.kw
+    if W is None or U is None or M is None or W.numel() != desc.cout * K or U.numel() != desc.cout * K or \
+            M.numel() != desc.cout * K or U.dtype != W.dtype:
+        raise SSError(SS_ERR_INVALID_ARG, "ss_mask_update_compress: W/U/M do not match the descriptor")
+    if packed is None:
+        packed = torch.empty(ss_packed_bytes(desc), dtype=torch.uint8, device=W.device)
+    elif packed.numel() * packed.element_size() < ss_packed_bytes(desc):
+        raise SSError(SS_ERR_INVALID_ARG, "ss_mask_update_compress: packed buffer too small")
+    bad = (ctypes.c_int32 * 2)(-1, -1)
+    st = _lib.ss_mask_update_compress(ctypes.byref(desc), _dev_ptr(W, "W", _T16), _dev_ptr(U, "U", _T16),
+                                      _dev_ptr(M, "M", (torch.uint8, torch.bool)), _dev_ptr(packed, "packed"), bad,
+                                      _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_mask_update_compress", detail=(bad[0], bad[1]) if st == SS_ERR_BAD_MASK else None)
     return packed
 
 

@@ -39,8 +39,25 @@ __global__ void write_header_kernel(uint32_t *hdr, uint32_t magic, int cout, int
 // A operand of a lane to come from, given that lane l of the B operand holds the 16 consecutive
 // reduction indices 32*ks + 16*(l/32) + [0,16).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void compress_kernel(const uint16_t *__restrict__ W, const uint8_t *__restrict__ M,
-                                                       uint8_t *__restrict__ packed, int cout, int K, int Mt, int Ks, int Kp)
+// binary32 sum of two 16-bit values, rounded to nearest even back to the storage type
+template <int DT>
+__device__ __forceinline__ uint32_t add16(uint32_t a, uint32_t b)
+{
+    if constexpr (DT == SS_F16) {
+        float s = (float)__builtin_bit_cast(_Float16, (uint16_t)a) + (float)__builtin_bit_cast(_Float16, (uint16_t)b);
+        return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)s);
+    } else {
+        float s = __builtin_bit_cast(float, a << 16) + __builtin_bit_cast(float, b << 16);
+        return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)s);
+    }
+}
+
+// UPD: the weights are first moved to V = W + U (written back over W; every element belongs to exactly one
+// thread's blocks), then V is packed.
+template <int DT, bool UPD>
+__global__ __launch_bounds__(256) void compress_kernel(uint16_t *__restrict__ W, const uint16_t *__restrict__ U,
+                                                       const uint8_t *__restrict__ M, uint8_t *__restrict__ packed,
+                                                       int cout, int K, int Mt, int Ks, int Kp)
 {
     int tid = blockIdx.x * 256 + threadIdx.x;
     int total = Mt * Ks * 64;
@@ -64,6 +81,12 @@ __global__ __launch_bounds__(256) void compress_kernel(const uint16_t *__restric
             size_t e = (size_t)row * K + 4 * (size_t)g;
             uint32_t m = *reinterpret_cast<const uint32_t *>(M + e);
             uint2 w = *reinterpret_cast<const uint2 *>(W + e);
+            if constexpr (UPD) {
+                const uint2 u = *reinterpret_cast<const uint2 *>(U + e);
+                w.x = add16<DT>(w.x & 0xFFFFu, u.x & 0xFFFFu) | (add16<DT>(w.x >> 16, u.x >> 16) << 16);
+                w.y = add16<DT>(w.y & 0xFFFFu, u.y & 0xFFFFu) | (add16<DT>(w.y >> 16, u.y >> 16) << 16);
+                *reinterpret_cast<uint2 *>(W + e) = w;
+            }
             bool ok = ((m & 0xFEFEFEFEu) == 0) && (__popc(m) == 2);
             if (ok) {
                 int i0 = (__ffs(m) - 1) >> 3;
@@ -177,21 +200,28 @@ extern "C" int ss_dense_bytes(const ss_weight_desc *desc, size_t *dense_bytes)
     return SS_OK;
 }
 
-extern "C" int ss_mask_compress(const ss_weight_desc *desc, const void *W, const uint8_t *M, void *packed,
-                                int32_t *bad_row_group, void *stream)
+static int compress_entry(const ss_weight_desc *desc, void *W, const void *U, const uint8_t *M, void *packed,
+                          int32_t *bad_row_group, void *stream)
 {
     int st = check_desc(desc, true);
     if (st != SS_OK) return st;
     if (!W || !M || !packed) return SS_ERR_INVALID_ARG;
-    if (!aligned(W, 8) || !aligned(M, 4) || !aligned(packed, 16)) return SS_ERR_INVALID_ARG;
+    if (!aligned(W, 8) || !aligned(M, 4) || !aligned(packed, 16) || (U && !aligned(U, 8))) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *p = static_cast<uint8_t *>(packed);
     write_header_kernel<<<1, 64, 0, s>>>(reinterpret_cast<uint32_t *>(p), kMagicSparse, desc->cout, desc->cin,
                                          desc->kh, desc->kw, desc->dtype, desc->korder, t.Mt, t.Ks);
     int total = t.Mt * t.Ks * 64;
-    compress_kernel<<<(total + 255) / 256, 256, 0, s>>>(static_cast<const uint16_t *>(W), M, p, desc->cout, t.K,
-                                                        t.Mt, t.Ks, t.Kp);
+    dim3 grid((total + 255) / 256), block(256);
+    uint16_t *w = static_cast<uint16_t *>(W);
+    const uint16_t *u = static_cast<const uint16_t *>(U);
+    if (!U)
+        compress_kernel<SS_F16, false><<<grid, block, 0, s>>>(w, nullptr, M, p, desc->cout, t.K, t.Mt, t.Ks, t.Kp);
+    else if (desc->dtype == SS_F16)
+        compress_kernel<SS_F16, true><<<grid, block, 0, s>>>(w, u, M, p, desc->cout, t.K, t.Mt, t.Ks, t.Kp);
+    else
+        compress_kernel<SS_BF16, true><<<grid, block, 0, s>>>(w, u, M, p, desc->cout, t.K, t.Mt, t.Ks, t.Kp);
     if (hipGetLastError() != hipSuccess) return SS_ERR_HIP;
     uint32_t first_bad = 0;
     if (hipMemcpyAsync(&first_bad, p + 4 * kHdrFirstBad, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return SS_ERR_HIP;
@@ -204,6 +234,19 @@ extern "C" int ss_mask_compress(const ss_weight_desc *desc, const void *W, const
         return SS_ERR_BAD_MASK;
     }
     return SS_OK;
+}
+
+extern "C" int ss_mask_compress(const ss_weight_desc *desc, const void *W, const uint8_t *M, void *packed,
+                                int32_t *bad_row_group, void *stream)
+{
+    return compress_entry(desc, const_cast<void *>(W), nullptr, M, packed, bad_row_group, stream);   // W is only read
+}
+
+extern "C" int ss_mask_update_compress(const ss_weight_desc *desc, void *W, const void *U, const uint8_t *M,
+                                       void *packed, int32_t *bad_row_group, void *stream)
+{
+    if (!U) return SS_ERR_INVALID_ARG;
+    return compress_entry(desc, W, U, M, packed, bad_row_group, stream);
 }
 
 extern "C" int ss_mask_decompress(const ss_weight_desc *desc, const void *packed, void *W_masked_out, void *stream)

@@ -112,3 +112,64 @@ def test_full_size_config1_compress(ss):
     expect = dl.tile(vals, meta, cin=L.cin, kh=L.kh, kw=L.kw, dtype=L.dtype, korder=L.korder)
     assert np.array_equal(packed.cpu().numpy(), expect)
     assert packed.numel() == 256 + 9 * (L.cout * L.K * 2) // 16
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_update_and_repack_match_oracle_bit_for_bit(ss, shape, dtype):
+    """W <- round16(W + U), packed <- compress(W, M): both bit for bit (values chosen without NaN results)."""
+    cout, cin, kh, kw, korder = shape
+    L = wl.Layer("t", N=1, H=4, W=4, cin=cin, cout=cout, kh=kh, kw=kw, dtype=dtype, korder=korder, mask="logits", seed=41)
+    d = wl.make_inputs(L)
+    rng = np.random.Generator(np.random.PCG64(7))
+    scale = np.float32(2.0 ** rng.integers(-12, 3, size=d["W"].shape))     # updates from far below an ulp to larger than W
+    Ub = wl.to_bits(rng.standard_normal(d["W"].shape, dtype=np.float32) * scale, dtype)
+    Wb = d["W"].copy()
+    edge = [(0x0001, 0x0001), (0x8000, 0x0000), (0x7BFF if dtype == wl.F16 else 0x7F7F, 0x7BFF if dtype == wl.F16 else 0x7F7F),
+            (0x3C00, 0xBC00), (0x03FF, 0x0001)]
+    for i, (a, b) in enumerate(edge[:min(len(edge), Wb.size)]):
+        Wb.reshape(-1)[i], Ub.reshape(-1)[i] = a, b
+    V = oracle.update(Wb, Ub, dtype)
+    desc = layer_desc(ss, L)
+    W, U, M = dev_bits(Wb, dtype), dev_bits(Ub, dtype), torch.from_numpy(d["M"]).cuda()
+    U_before = U.clone()
+    packed = ss.ss_mask_update_compress(desc, W, U, M)
+    assert np.array_equal(host_bits(W), V)
+    assert torch.equal(U.view(torch.int16), U_before.view(torch.int16))
+    vals, meta = oracle.compress(V, d["M"])
+    assert np.array_equal(packed.cpu().numpy(), dl.tile(vals, meta, cin=cin, kh=kh, kw=kw, dtype=dtype, korder=korder))
+    # the same bytes as packing the updated weights from scratch
+    assert torch.equal(packed, ss.ss_mask_compress(desc, W, M))
+
+
+def test_convolution_after_an_update_uses_the_new_weights(ss):
+    L = wl.Layer("t", N=2, H=9, W=9, cin=64, cout=96, kh=3, kw=3, stride=1, pad=1, dtype=wl.BF16, act=wl.ACT_RELU,
+                 mask="logits", seed=12)
+    d = wl.make_inputs(L)
+    rng = np.random.Generator(np.random.PCG64(8))
+    Ub = wl.to_bits(rng.standard_normal(d["W"].shape, dtype=np.float32) * np.float32(0.05), L.dtype)
+    desc = layer_desc(ss, L)
+    W, U, M = dev_bits(d["W"], L.dtype), dev_bits(Ub, L.dtype), torch.from_numpy(d["M"]).cuda()
+    packed = ss.ss_mask_update_compress(desc, W, U, M)
+    y = ss.ss_conv2d_fwd(desc, dev_bits(d["x"], L.dtype), packed, torch.from_numpy(d["bias"]).cuda(), (1, 1), (1, 1), L.act)
+    V = oracle.update(d["W"], Ub, L.dtype)
+    ref = oracle.conv2d(d["x"], V, d["M"], cin=L.cin, kh=3, kw=3, dtype=L.dtype, bias=d["bias"], pad=(1, 1), act=L.act)
+    from helpers import check_close
+    check_close(y, ref, "conv after update")
+    old = oracle.conv2d(d["x"], d["W"], d["M"], cin=L.cin, kh=3, kw=3, dtype=L.dtype, bias=d["bias"], pad=(1, 1), act=L.act)
+    assert np.linalg.norm(ref - old) / np.linalg.norm(old) > 0.05          # the update is visible at this tolerance
+
+
+def test_update_compress_argument_and_mask_errors(ss):
+    L = wl.Layer("t", N=1, H=2, W=2, cin=16, cout=40, kh=1, kw=1, mask="logits", seed=1)
+    d = wl.make_inputs(L)
+    desc = layer_desc(ss, L)
+    W, M = dev_bits(d["W"], L.dtype), torch.from_numpy(d["M"]).cuda()
+    with pytest.raises(ss.SSError):
+        ss.ss_mask_update_compress(desc, W, W[:10], M)
+    Mb = d["M"].copy()
+    Mb[3, 4:8] = [1, 1, 1, 0]
+    U = torch.zeros_like(W)
+    with pytest.raises(ss.SSError) as e:
+        ss.ss_mask_update_compress(desc, W, U, torch.from_numpy(Mb).cuda())
+    assert e.value.status == ss.SS_ERR_BAD_MASK and e.value.detail == (3, 1)
