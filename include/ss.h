@@ -202,6 +202,19 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
                             int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
                             void *y, void *workspace, size_t ws_bytes, void *stream);
 
+/*
+ * Max pooling of NHWC 16-bit activations with a k x k window (the pooling between the stem and the
+ * first residual block of the ResNet models of Sec. 4), so that a chained convolution stack stays
+ * inside the library.  Positions outside the image do not take part (with 2*pad <= k every window
+ * holds at least one pixel); the output element is the bit pattern of the largest input (-0 < +0 is
+ * not distinguished: whichever comes first in row-major window order stays); a NaN wins.
+ *   x  [N][H][Wd][C]    16-bit, dtype, 16-byte aligned, C % 8 == 0 (else SS_ERR_UNSUPPORTED)  (read only)
+ *   y  [N][Ho][Wo][C]   Ho = (H + 2*pad - k) / stride + 1, same for Wo                      (written)
+ * Asynchronous on `stream`.
+ */
+int ss_maxpool2d(const void *x, int32_t N, int32_t H, int32_t Wd, int32_t C, int32_t dtype, int32_t k,
+                 int32_t stride, int32_t pad, void *y, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,6 +57,8 @@ def _load():
         lib.ss_oracle_decompress.argtypes = [p, p, i64, i64, p]
         lib.ss_oracle_update.restype = None
         lib.ss_oracle_update.argtypes = [p, p, i64, ctypes.c_int]
+        lib.ss_oracle_maxpool2d.restype = ctypes.c_int
+        lib.ss_oracle_maxpool2d.argtypes = [p, i64, i64, i64, i64, ctypes.c_int, i64, i64, i64, p]
         lib.ss_oracle_conv2d.restype = ctypes.c_int
         lib.ss_oracle_conv2d.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
                                          ctypes.c_int, ctypes.c_int, p, p, i64, i64, i64, i64,
@@ -193,3 +195,15 @@ def conv2d_points(x_bits, W_bits, M, flat_idx, *, cin, kh, kw, korder=K_CRS, dty
     if st:
         raise ValueError(f"oracle conv2d_points failed (status {st})")
     return out
+
+
+def maxpool2d(x_bits, *, dtype=F16, k=3, stride=2, pad=1) -> np.ndarray:
+    """NHWC max pooling on 16-bit patterns; positions outside the image do not take part."""
+    x_bits = _c(x_bits, np.uint16)
+    N, H, Wd, C = x_bits.shape
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (Wd + 2 * pad - k) // stride + 1
+    y = np.empty((N, Ho, Wo, C), dtype=np.uint16)
+    st = _load().ss_oracle_maxpool2d(_ptr(x_bits), N, H, Wd, C, dtype, k, stride, pad, _ptr(y))
+    if st:
+        raise ValueError(f"oracle maxpool2d failed (status {st})")
+    return y

@@ -304,3 +304,34 @@ int ss_oracle_conv2d_points(const uint16_t *x, int64_t N, int64_t H, int64_t Wd,
     }
     return 0;
 }
+
+/* Max pooling, NHWC, k x k window, given stride and symmetric zero-extent padding: the maximum over the window
+ * positions that lie inside the image (the pooling layer between the stem and the first residual block of the
+ * ResNet models the paper evaluates, Sec. 4).  Values are compared as their exact fp64 widenings; the output is the
+ * 16-bit pattern of the winner (first one in row-major window order among equals); a NaN, once met, stays. */
+int ss_oracle_maxpool2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_t C, int dtype,
+                        int64_t k, int64_t stride, int64_t pad, uint16_t *y)
+{
+    int64_t Ho = (H + 2 * pad - k) / stride + 1, Wo = (Wd + 2 * pad - k) / stride + 1;
+    if (H + 2 * pad < k || Wd + 2 * pad < k || Ho <= 0 || Wo <= 0) return 3;
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t ho = 0; ho < Ho; ho++)
+            for (int64_t wo = 0; wo < Wo; wo++)
+                for (int64_t c = 0; c < C; c++) {
+                    int have = 0;
+                    uint16_t best = 0;
+                    double bestv = 0.0;
+                    for (int64_t r = 0; r < k; r++)
+                        for (int64_t t = 0; t < k; t++) {
+                            int64_t ih = ho * stride - pad + r, iw = wo * stride - pad + t;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                            uint16_t b = x[((n * H + ih) * Wd + iw) * C + c];
+                            double v = ss_oracle_bits_to_double(b, dtype);
+                            if (!have) { have = 1; best = b; bestv = v; continue; }
+                            if (bestv != bestv) continue;                       /* NaN stays */
+                            if (v != v || v > bestv) { best = b; bestv = v; }
+                        }
+                    y[((n * Ho + ho) * Wo + wo) * C + c] = have ? best : 0;
+                }
+    return 0;
+}
