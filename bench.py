@@ -7,7 +7,7 @@ already resident in device memory; the weight compressor is a one-off per weight
 timed separately.  The dense twin is timed the same way for the speed-up ratio, and the CPU
 oracle is timed on the host cores as a reported baseline.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail]   (--table: per-layer report,
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail | --trunk]   (--table: per-layer report,
                                                                           --tail: fused residual tail report)
 """
 from __future__ import annotations
@@ -230,6 +230,23 @@ def print_tail_table(torch, ss, wl, steps, warmup):
         torch.cuda.empty_cache()
 
 
+def print_trunk(torch, ss, wl, batch=64, image=224):
+    """End-to-end ResNet-50 convolution trunk (53 convolutions + max pool, real dataflow, fused residual tails),
+    replayed as one HIP graph: images per second on the sparse path and on the dense twin."""
+    from paper_2411_00288_amd import resnet50
+    print(f"## ResNet-50 convolution trunk, batch {batch}, {image}x{image}, bf16, synthetic weights: stem (dense) -> max pool -> "
+          "16 bottlenecks; 48 convolutions 2:4-masked, stem and 4 shortcut convolutions dense; add + ReLU fused into conv3")
+    for sparse in (True, False):
+        t = resnet50.Trunk(batch=batch, image=image, dtype=wl.BF16, sparse=sparse)
+        t.input.copy_(torch.randn(t.input.shape, device="cuda").to(torch.bfloat16))
+        ms = median_time(torch, t.forward, 5, 2, reps=5)
+        stem = median_time(torch, t.launches[0], 20, 3, reps=3)
+        print(f"{'2:4 sparse path' if sparse else 'dense twin     '}: {ms:8.3f} ms per batch  {batch / ms * 1e3:9.0f} images/s  "
+              f"{t.dense_equiv_flop() / ms / 1e9:7.1f} TFLOP/s dense-equivalent   (stem alone {stem * 1e3:6.1f} us)", flush=True)
+        del t
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,6 +255,7 @@ def main():
     ap.add_argument("--table", action="store_true", help="per-layer report for all configurations instead of the JSON line")
     ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
+    ap.add_argument("--trunk", action="store_true", help="end-to-end ResNet-50 convolution trunk (images/s) instead of the JSON line")
     ap.add_argument("--tail", action="store_true", help="report of the fused residual / activation tail instead of the JSON line")
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
@@ -259,6 +277,9 @@ def main():
     from paper_2411_00288_amd import workloads as wl
     torch.cuda.set_device(0)
 
+    if args.trunk:
+        print_trunk(torch, ss, wl)
+        return
     if args.tail:
         print_tail_table(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50))
         return

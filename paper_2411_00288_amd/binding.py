@@ -22,7 +22,7 @@ SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
-           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress"]
+           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d"]
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -51,6 +51,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_dense_bytes.argtypes = [dp, ctypes.POINTER(sz)]
     lib.ss_mask_compress.argtypes = [dp, vp, vp, vp, ctypes.POINTER(i32), vp]
     lib.ss_mask_update_compress.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(i32), vp]
+    lib.ss_maxpool2d.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_mask_decompress.argtypes = [dp, vp, vp, vp]
     lib.ss_dense_pack.argtypes = [dp, vp, vp, vp, vp]
     lib.ss_conv2d_workspace_bytes.argtypes = [dp, i32, i32, i32, i32, i32, i32, i32, ctypes.POINTER(sz)]
@@ -282,3 +283,21 @@ def ss_conv2d_dense_res_fwd(desc, x, dense, bias=None, residual=None, stride=(1,
     """The dense-MFMA twin of ss_conv2d_res_fwd."""
     return _conv(_lib.ss_conv2d_dense_res_fwd, "ss_conv2d_dense_res_fwd", desc, x, dense, bias, stride, pad, act, y,
                  workspace, stream, residual, True)
+
+
+def ss_maxpool2d(x: torch.Tensor, k: int = 3, stride: int = 2, pad: int = 1, y: torch.Tensor | None = None,
+                 stream=None) -> torch.Tensor:
+    """NHWC max pooling of a 16-bit tensor (positions outside the image do not take part)."""
+    if x is None or x.dim() != 4 or x.dtype not in _T16 or stride <= 0:
+        raise SSError(SS_ERR_INVALID_ARG, "ss_maxpool2d: x must be a 16-bit NHWC tensor")
+    N, H, W, C = x.shape
+    shp = (N, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1, C)
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != shp or y.dtype != x.dtype:
+        raise SSError(SS_ERR_INVALID_ARG, f"ss_maxpool2d: y must be {shp} {x.dtype}")
+    st = _lib.ss_maxpool2d(_dev_ptr(x, "x"), N, H, W, C, SS_F16 if x.dtype == torch.float16 else SS_BF16, k, stride, pad,
+                           _dev_ptr(y, "y"), _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_maxpool2d")
+    return y

@@ -138,6 +138,18 @@ def make_inputs(L: Layer) -> dict:
     return {"W": W_bits, "M": M, "x": to_bits(x, L.dtype), "bias": bias}
 
 
+def make_weights(L: Layer, scale: float = 1.0) -> dict:
+    """Only (W_bits, M, bias) of a layer, for a chained stack whose activations come from the layer before.
+    `scale` multiplies the He-normal weights (the last convolution of a residual branch is drawn smaller so that
+    the un-normalised sum of sixteen branches stays in range)."""
+    rng = np.random.Generator(np.random.PCG64(L.seed))
+    w = rng.standard_normal((L.cout, L.cin, L.kh, L.kw), dtype=np.float32) * np.float32(scale * np.sqrt(2.0 / L.K))
+    bias = rng.standard_normal(L.cout, dtype=np.float32) * np.float32(0.1)
+    W_bits = flatten_weight(to_bits(w, L.dtype), L.korder)
+    M = None if L.mask == "none" else mask_top2(W_bits, L.dtype)
+    return {"W": W_bits, "M": M, "bias": bias}
+
+
 def make_small_int_inputs(L: Layer, seed: int = 0) -> dict:
     """Small-integer tensors (w in {-1,0,1}, x in {0,1,2}, integer bias) for which no rounding
     occurs anywhere as long as every partial sum stays below the storage type's exact-integer
