@@ -190,6 +190,17 @@ def print_table(torch, ss, wl, steps, warmup, cold, only=""):
             print(f"{L.name:34s} {L.count:2d} {r['gflop']:8.2f} {r.get('sparse_us', float('nan')):10.2f} {r['dense_us']:9.2f} "
                   f"{r.get('speedup', float('nan')):7.2f} {r['tflops']:8.1f} {r['gbs']:7.0f} {r['t_floor_us']:8.2f} {r['t_floor_us'] / t_used:5.2f}", flush=True)
         print(f"{'total (x count)':34s}    {'':8s} {tot_s:10.1f} {tot_d:9.1f} {tot_d / tot_s:7.2f} {'':8s} {'':7s} {tot_f:8.1f} {tot_f / tot_s:5.2f}", flush=True)
+        if "ConvNeXt" in title and not only:
+            # the block's grouped convolution stays dense in the paper and runs through the dedicated depthwise kernel
+            N, H, C = layers[0].N, layers[0].H, 96
+            x = torch.randn((N, H, H, C), device="cuda").to(torch.bfloat16)
+            w = (torch.randn((7, 7, C), device="cuda") * (2.0 / 49) ** 0.5).to(torch.bfloat16)
+            b = torch.randn(C, device="cuda") * 0.1
+            y = torch.empty_like(x)
+            t = median_time(torch, lambda: ss.ss_dwconv2d_fwd(x, w, b, (3, 3), y=y), steps, warmup, reps=3) * 1e3
+            nbytes, flop = 2 * x.numel() * 2, 2.0 * x.numel() * 49
+            print(f"{'cnx_dw_7x7_96 (dense, depthwise)':34s} {3:2d} {flop / 1e9:8.2f} {'':>10s} {t:9.2f} {'':>7s} {flop / t / 1e6:8.1f} "
+                  f"{nbytes / t / 1e3:7.0f} {nbytes / HBM_PEAK_GBS / 1e3:8.2f} {nbytes / HBM_PEAK_GBS / 1e3 / t:5.2f}", flush=True)
     return rows
 
 

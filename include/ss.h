@@ -215,6 +215,24 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
 int ss_maxpool2d(const void *x, int32_t N, int32_t H, int32_t Wd, int32_t C, int32_t dtype, int32_t k,
                  int32_t stride, int32_t pad, void *y, void *stream);
 
+/*
+ * Depthwise convolution (one kh x kw filter per channel), stride 1: the grouped convolutions that
+ * the paper leaves dense (Sec. 4, "Architectures"), e.g. the 7x7 of a ConvNeXt block, so that the
+ * dense layers of such a block are measured next to its masked ones.
+ *     y[n,h,w,c] = act( bias[c] + sum_{r,t} w[r][t][c] * x[n, h - pad_h + r, w - pad_w + t, c] )
+ * fp32 accumulation, one rounding to the 16-bit type at the store.
+ *   x     [N][H][Wd][C]   16-bit, dtype, 16-byte aligned                          (read only)
+ *   w     [kh][kw][C]     16-bit, dtype (channel fastest), 16-byte aligned         (read only)
+ *   bias  [C] fp32 or NULL                                                        (read only)
+ *   act   SS_ACT_NONE | SS_ACT_RELU
+ *   y     [N][Ho][Wo][C], Ho = H + 2*pad_h - kh + 1, Wo = Wd + 2*pad_w - kw + 1    (written)
+ * SS_ERR_UNSUPPORTED unless C % 8 == 0, kw in {3, 5, 7} and kh*kw*C*2 <= 65536 bytes.
+ * Asynchronous on `stream`.
+ */
+int ss_dwconv2d_fwd(const void *x, int32_t N, int32_t H, int32_t Wd, int32_t C, int32_t dtype, const void *w,
+                    const float *bias, int32_t kh, int32_t kw, int32_t pad_h, int32_t pad_w, int32_t act,
+                    void *y, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,6 +57,8 @@ def _load():
         lib.ss_oracle_decompress.argtypes = [p, p, i64, i64, p]
         lib.ss_oracle_update.restype = None
         lib.ss_oracle_update.argtypes = [p, p, i64, ctypes.c_int]
+        lib.ss_oracle_dwconv2d.restype = ctypes.c_int
+        lib.ss_oracle_dwconv2d.argtypes = [p, i64, i64, i64, i64, ctypes.c_int, p, p, i64, i64, i64, i64, ctypes.c_int, p]
         lib.ss_oracle_maxpool2d.restype = ctypes.c_int
         lib.ss_oracle_maxpool2d.argtypes = [p, i64, i64, i64, i64, ctypes.c_int, i64, i64, i64, p]
         lib.ss_oracle_conv2d.restype = ctypes.c_int
@@ -206,4 +208,23 @@ def maxpool2d(x_bits, *, dtype=F16, k=3, stride=2, pad=1) -> np.ndarray:
     st = _load().ss_oracle_maxpool2d(_ptr(x_bits), N, H, Wd, C, dtype, k, stride, pad, _ptr(y))
     if st:
         raise ValueError(f"oracle maxpool2d failed (status {st})")
+    return y
+
+
+def dwconv2d(x_bits, w_bits, *, dtype=F16, bias=None, pad=(0, 0), act=ACT_NONE) -> np.ndarray:
+    """Depthwise convolution, stride 1: x NHWC, w [kh, kw, C] (16-bit patterns), fp64 result, not rounded."""
+    x_bits, w_bits = _c(x_bits, np.uint16), _c(w_bits, np.uint16)
+    N, H, Wd, C = x_bits.shape
+    kh, kw, c2 = w_bits.shape
+    assert c2 == C
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    Ho, Wo = H + 2 * pad[0] - kh + 1, Wd + 2 * pad[1] - kw + 1
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    y = np.empty((N, Ho, Wo, C), dtype=np.float64)
+    st = _load().ss_oracle_dwconv2d(_ptr(x_bits), N, H, Wd, C, dtype, _ptr(w_bits), _ptr(bias), kh, kw, pad[0], pad[1],
+                                    act, _ptr(y))
+    if st:
+        raise ValueError(f"oracle dwconv2d failed (status {st})")
     return y

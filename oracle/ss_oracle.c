@@ -335,3 +335,34 @@ int ss_oracle_maxpool2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int
                 }
     return 0;
 }
+
+/* Depthwise convolution (one filter per channel; the grouped convolutions that stay dense in the paper, Sec. 4),
+ * stride 1, zero padding, NHWC.  Eq. (4) restricted to its diagonal: the output channel c only sees input channel c.
+ *   x [N][H][Wd][C], w [kh][kw][C] (channel fastest), bias [C] fp32 or NULL, y [N][Ho][Wo][C] fp64, not rounded. */
+int ss_oracle_dwconv2d(const uint16_t *x, int64_t N, int64_t H, int64_t Wd, int64_t C, int dtype,
+                       const uint16_t *w, const float *bias, int64_t kh, int64_t kw, int64_t pad_h, int64_t pad_w,
+                       int act, double *y)
+{
+    int64_t Ho = H + 2 * pad_h - kh + 1, Wo = Wd + 2 * pad_w - kw + 1;
+    if (Ho <= 0 || Wo <= 0) return 3;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t ho = 0; ho < Ho; ho++)
+            for (int64_t wo = 0; wo < Wo; wo++)
+                for (int64_t c = 0; c < C; c++) {
+                    double acc = 0.0;
+                    for (int64_t r = 0; r < kh; r++) {
+                        int64_t ih = ho - pad_h + r;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int64_t t = 0; t < kw; t++) {
+                            int64_t iw = wo - pad_w + t;
+                            if (iw < 0 || iw >= Wd) continue;
+                            acc += ss_oracle_bits_to_double(w[(r * kw + t) * C + c], dtype) *
+                                   ss_oracle_bits_to_double(x[((n * H + ih) * Wd + iw) * C + c], dtype);
+                        }
+                    }
+                    if (bias) acc += (double)bias[c];
+                    y[((n * Ho + ho) * Wo + wo) * C + c] = layer_tail(acc, act);
+                }
+    return 0;
+}

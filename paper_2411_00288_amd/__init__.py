@@ -10,7 +10,7 @@ from __future__ import annotations
 import importlib
 
 _BINDING_NAMES = {
-    "ss_status_string", "status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_update_compress", "ss_mask_decompress", "ss_maxpool2d",
+    "ss_status_string", "status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_update_compress", "ss_mask_decompress", "ss_maxpool2d", "ss_dwconv2d_fwd",
     "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd", "ss_conv2d_res_fwd",
     "ss_conv2d_dense_res_fwd", "make_desc", "out_shape", "prepare_conv2d",
     "ss_weight_desc", "SSError", "torch_dtype", "EXPORTS", "LIB_PATH",

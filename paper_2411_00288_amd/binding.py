@@ -22,7 +22,7 @@ SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
-           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d"]
+           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd"]
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -52,6 +52,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_mask_compress.argtypes = [dp, vp, vp, vp, ctypes.POINTER(i32), vp]
     lib.ss_mask_update_compress.argtypes = [dp, vp, vp, vp, vp, ctypes.POINTER(i32), vp]
     lib.ss_maxpool2d.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_dwconv2d_fwd.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_mask_decompress.argtypes = [dp, vp, vp, vp]
     lib.ss_dense_pack.argtypes = [dp, vp, vp, vp, vp]
     lib.ss_conv2d_workspace_bytes.argtypes = [dp, i32, i32, i32, i32, i32, i32, i32, ctypes.POINTER(sz)]
@@ -300,4 +301,27 @@ def ss_maxpool2d(x: torch.Tensor, k: int = 3, stride: int = 2, pad: int = 1, y: 
                            _dev_ptr(y, "y"), _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_maxpool2d")
+    return y
+
+
+def ss_dwconv2d_fwd(x: torch.Tensor, w: torch.Tensor, bias: torch.Tensor | None = None, pad=(0, 0), act=SS_ACT_NONE,
+                    y: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Depthwise convolution, stride 1: x NHWC 16-bit, w [kh, kw, C] of the same dtype -> y NHWC."""
+    if x is None or w is None or x.dim() != 4 or w.dim() != 3 or w.shape[2] != x.shape[3] or w.dtype != x.dtype or \
+            x.dtype not in (torch.float16, torch.bfloat16):
+        raise SSError(SS_ERR_INVALID_ARG, "ss_dwconv2d_fwd: x must be NHWC 16-bit and w [kh, kw, C] of the same dtype")
+    N, H, W, C = x.shape
+    kh, kw = int(w.shape[0]), int(w.shape[1])
+    shp = (N, H + 2 * pad[0] - kh + 1, W + 2 * pad[1] - kw + 1, C)
+    if shp[1] <= 0 or shp[2] <= 0:
+        raise SSError(SS_ERR_INVALID_ARG, "ss_dwconv2d_fwd: empty output")
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != shp or y.dtype != x.dtype:
+        raise SSError(SS_ERR_INVALID_ARG, f"ss_dwconv2d_fwd: y must be {shp} {x.dtype}")
+    st = _lib.ss_dwconv2d_fwd(_dev_ptr(x, "x"), N, H, W, C, SS_F16 if x.dtype == torch.float16 else SS_BF16,
+                              _dev_ptr(w, "w"), _dev_ptr(bias, "bias", (torch.float32,), allow_none=True), kh, kw,
+                              pad[0], pad[1], act, _dev_ptr(y, "y"), _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_dwconv2d_fwd")
     return y

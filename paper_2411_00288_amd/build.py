@@ -9,7 +9,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libss.so"
-SOURCES = ["ss_pack.hip", "ss_conv.hip", "ss_pool.hip"]
+SOURCES = ["ss_pack.hip", "ss_conv.hip", "ss_pool.hip", "ss_dwconv.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          # packed-fp32 instructions have produced silently wrong results on the test machines
