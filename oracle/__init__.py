@@ -21,7 +21,7 @@ _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "ss_oracle.c"
 _LIB = _HERE / "libss_oracle.so"
 
-F16, BF16 = 0, 1
+F16, BF16, I8 = 0, 1, 2
 K_CRS, K_RSC = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
@@ -69,6 +69,16 @@ def _load():
         lib.ss_oracle_conv2d_points.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64,
                                                 ctypes.c_int, ctypes.c_int, p, p, i64, i64, i64, i64,
                                                 ctypes.c_int, p, i64, p]
+        lib.ss_oracle_compress8.restype = ctypes.c_int
+        lib.ss_oracle_compress8.argtypes = [p, p, i64, i64, p, p]
+        lib.ss_oracle_decompress8.restype = None
+        lib.ss_oracle_decompress8.argtypes = [p, p, i64, i64, p]
+        lib.ss_oracle_conv2d_q8.restype = ctypes.c_int
+        lib.ss_oracle_conv2d_q8.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64, ctypes.c_int, p, p,
+                                            i64, i64, i64, i64, ctypes.c_int, p]
+        lib.ss_oracle_conv2d_q8_points.restype = ctypes.c_int
+        lib.ss_oracle_conv2d_q8_points.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64, ctypes.c_int, p, p,
+                                                   i64, i64, i64, i64, ctypes.c_int, p, i64, p]
         _lib = lib
     return _lib
 
@@ -228,3 +238,78 @@ def dwconv2d(x_bits, w_bits, *, dtype=F16, bias=None, pad=(0, 0), act=ACT_NONE) 
     if st:
         raise ValueError(f"oracle dwconv2d failed (status {st})")
     return y
+
+
+# ---------------------------------------------------------------------------------------------
+# 8-bit integer precision point
+# ---------------------------------------------------------------------------------------------
+def compress8(W_q, M):
+    """Canonical structured form of an int8 matrix: (vals int8 [cout, K/2], meta uint8 [cout, K/4])."""
+    W_q, M = _c(W_q, np.int8), _c(M, np.uint8)
+    cout, K = W_q.shape
+    assert M.shape == (cout, K)
+    if K % 4:
+        raise ValueError("K % 4 != 0")
+    vals = np.zeros((cout, K // 2), dtype=np.int8)
+    meta = np.zeros((cout, K // 4), dtype=np.uint8)
+    st = _load().ss_oracle_compress8(_ptr(W_q), _ptr(M), cout, K, _ptr(vals), _ptr(meta))
+    if st:
+        raise ValueError(f"invalid 2:4 mask (status {st})")
+    return vals, meta
+
+
+def decompress8(vals, meta) -> np.ndarray:
+    vals, meta = _c(vals, np.int8), _c(meta, np.uint8)
+    cout, G = meta.shape
+    out = np.empty((cout, 4 * G), dtype=np.int8)
+    _load().ss_oracle_decompress8(_ptr(vals), _ptr(meta), cout, 4 * G, _ptr(out))
+    return out
+
+
+def _q8_args(x_q, W_q, M, scale, bias, cin, kh, kw):
+    x_q, W_q = _c(x_q, np.int8), _c(W_q, np.int8)
+    N, H, Wd, c = x_q.shape
+    assert c == cin
+    cout, K = W_q.shape
+    assert K == cin * kh * kw
+    if M is not None:
+        M = _c(M, np.uint8)
+        assert M.shape == (cout, K)
+    if scale is not None:
+        scale = _c(scale, np.float32)
+        assert scale.shape == (cout,)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+        assert bias.shape == (cout,)
+    return x_q, W_q, M, scale, bias, N, H, Wd, cout
+
+
+def conv2d_q8(x_q, W_q, M, *, cin, kh, kw, korder=K_CRS, scale=None, bias=None, stride=(1, 1), pad=(0, 0),
+              act=ACT_NONE) -> np.ndarray:
+    """Integer masked convolution: exact int64 sums, then act(scale[o] * sum + bias[o]) in fp64, not rounded."""
+    x_q, W_q, M, scale, bias, N, H, Wd, cout = _q8_args(x_q, W_q, M, scale, bias, cin, kh, kw)
+    Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    y = np.empty((N, Ho, Wo, cout), dtype=np.float64)
+    st = _load().ss_oracle_conv2d_q8(_ptr(x_q), N, H, Wd, cin, _ptr(W_q), _ptr(M), cout, kh, kw, korder, _ptr(scale),
+                                     _ptr(bias), stride[0], stride[1], pad[0], pad[1], act, _ptr(y))
+    if st:
+        raise ValueError(f"oracle conv2d_q8 failed (status {st})")
+    return y
+
+
+def conv2d_q8_points(x_q, W_q, M, flat_idx, *, cin, kh, kw, korder=K_CRS, scale=None, bias=None, stride=(1, 1),
+                     pad=(0, 0), act=ACT_NONE) -> np.ndarray:
+    """The same definition at sampled flat NHWC output indices only."""
+    x_q, W_q, M, scale, bias, N, H, Wd, cout = _q8_args(x_q, W_q, M, scale, bias, cin, kh, kw)
+    flat_idx = _c(flat_idx, np.int64)
+    Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
+    assert flat_idx.min() >= 0 and flat_idx.max() < N * Ho * Wo * cout
+    out = np.empty(flat_idx.shape, dtype=np.float64)
+    st = _load().ss_oracle_conv2d_q8_points(_ptr(x_q), N, H, Wd, cin, _ptr(W_q), _ptr(M), cout, kh, kw, korder,
+                                            _ptr(scale), _ptr(bias), stride[0], stride[1], pad[0], pad[1], act,
+                                            _ptr(flat_idx), flat_idx.size, _ptr(out))
+    if st:
+        raise ValueError(f"oracle conv2d_q8_points failed (status {st})")
+    return out

@@ -35,6 +35,8 @@
  * gelu(z) - gelu(-z) = z, tabulated values of Phi, and a library normal CDF.  No function here
  * is "parity unpinned".  The weight update's rounding is pinned against numpy's float16 and torch's bfloat16
  * conversions (all 65536 patterns x a spread of addends: ties, carries, subnormals, overflow).
+ * The 8-bit integer functions are pinned against an int64 unfold + matmul in numpy, a float64 library convolution
+ * (exact on these integers), the 16-bit functions above on the same small integers, and closed forms.
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -301,6 +303,119 @@ int ss_oracle_conv2d_points(const uint16_t *x, int64_t N, int64_t H, int64_t Wd,
         if (bias) acc += (double)bias[o];
         if (residual) acc += ss_oracle_bits_to_double(residual[yi], dtype);
         out[i] = layer_tail(acc, act);
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * 8-bit integer precision point.  The same definitions (Fig. 1 for the representation, Eq. (4) with
+ * H <- M (.) W, Eq. 6, for the convolution) on signed 8-bit operands: weights and activations are the
+ * integers their bytes encode, every product and the running sum are exact (int64), and the layer output is
+ *     y = act( scale[o] * acc + bias[o] )
+ * in fp64, with a per-output-channel fp32 scale (the product of the weight and activation quantisation steps
+ * of a symmetric quantiser; NULL means 1).  The paper itself stops at 16-bit floats; this is the integer
+ * analogue of its Eq. (6), not something it defines.
+ * --------------------------------------------------------------------------------------------- */
+
+/* Fig. 1 on bytes: vals[o][2g], vals[o][2g+1] = the two kept bytes of group g in ascending position order,
+ * meta[o][g] = i0 | (i1 << 2). */
+int ss_oracle_compress8(const uint8_t *W, const uint8_t *M, int64_t cout, int64_t K, uint8_t *vals, uint8_t *meta)
+{
+    int st = ss_oracle_mask_check(M, cout, K, NULL, NULL);
+    if (st) return st;
+    int64_t G = K / 4;
+    for (int64_t o = 0; o < cout; o++) {
+        for (int64_t g = 0; g < G; g++) {
+            int pos[2], n = 0;
+            for (int e = 0; e < 4; e++)
+                if (M[o * K + 4 * g + e]) pos[n++] = e;
+            vals[o * (K / 2) + 2 * g + 0] = W[o * K + 4 * g + pos[0]];
+            vals[o * (K / 2) + 2 * g + 1] = W[o * K + 4 * g + pos[1]];
+            meta[o * G + g] = (uint8_t)(pos[0] | (pos[1] << 2));
+        }
+    }
+    return 0;
+}
+
+void ss_oracle_decompress8(const uint8_t *vals, const uint8_t *meta, int64_t cout, int64_t K, uint8_t *Wm)
+{
+    int64_t G = K / 4;
+    for (int64_t o = 0; o < cout; o++) {
+        for (int64_t g = 0; g < G; g++) {
+            for (int e = 0; e < 4; e++) Wm[o * K + 4 * g + e] = 0;
+            int i0 = meta[o * G + g] & 3, i1 = (meta[o * G + g] >> 2) & 3;
+            Wm[o * K + 4 * g + i0] = vals[o * (K / 2) + 2 * g + 0];
+            Wm[o * K + 4 * g + i1] = vals[o * (K / 2) + 2 * g + 1];
+        }
+    }
+}
+
+/* One output of the integer convolution: the exact sum of Eq. (4) / Eq. (6) at (n, ho, wo, o). */
+static int64_t q8_sum(const int8_t *x, int64_t H, int64_t Wd, int64_t cin, const int8_t *W, const uint8_t *M,
+                      int64_t kh, int64_t kw, int korder, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                      int64_t pad_w, int64_t n, int64_t ho, int64_t wo, int64_t o)
+{
+    int64_t K = cin * kh * kw, acc = 0;
+    for (int64_t c = 0; c < cin; c++)
+        for (int64_t r = 0; r < kh; r++) {
+            int64_t ih = ho * stride_h - pad_h + r;
+            if (ih < 0 || ih >= H) continue;                  /* zero padding */
+            for (int64_t t = 0; t < kw; t++) {
+                int64_t iw = wo * stride_w - pad_w + t;
+                if (iw < 0 || iw >= Wd) continue;             /* zero padding */
+                int64_t k = kflat(korder, c, r, t, cin, kh, kw);
+                if (M != NULL && !M[o * K + k]) continue;     /* M (.) W */
+                acc += (int64_t)W[o * K + k] * (int64_t)x[((n * H + ih) * Wd + iw) * cin + c];
+            }
+        }
+    return acc;
+}
+
+/*   x [N][H][Wd][cin] int8, W [cout][K] int8, M [cout][K] 0/1 bytes or NULL, scale [cout] fp32 or NULL (= 1),
+ *   bias [cout] fp32 or NULL, y [N][Ho][Wo][cout] fp64, not rounded. */
+int ss_oracle_conv2d_q8(const int8_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin, const int8_t *W,
+                        const uint8_t *M, int64_t cout, int64_t kh, int64_t kw, int korder, const float *scale,
+                        const float *bias, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                        int act, double *y)
+{
+    int64_t Ho = (H + 2 * pad_h - kh) / stride_h + 1;
+    int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
+    if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t ho = 0; ho < Ho; ho++)
+            for (int64_t wo = 0; wo < Wo; wo++)
+                for (int64_t o = 0; o < cout; o++) {
+                    int64_t acc = q8_sum(x, H, Wd, cin, W, M, kh, kw, korder, stride_h, stride_w, pad_h, pad_w,
+                                         n, ho, wo, o);
+                    double z = (double)acc * (scale ? (double)scale[o] : 1.0);
+                    if (bias) z += (double)bias[o];
+                    y[((n * Ho + ho) * Wo + wo) * cout + o] = layer_tail(z, act);
+                }
+    return 0;
+}
+
+/* The same at sampled outputs (flat NHWC indices), for sizes the full tensor would take too long. */
+int ss_oracle_conv2d_q8_points(const int8_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin, const int8_t *W,
+                               const uint8_t *M, int64_t cout, int64_t kh, int64_t kw, int korder,
+                               const float *scale, const float *bias, int64_t stride_h, int64_t stride_w,
+                               int64_t pad_h, int64_t pad_w, int act, const int64_t *flat_idx, int64_t npts,
+                               double *out)
+{
+    int64_t Ho = (H + 2 * pad_h - kh) / stride_h + 1;
+    int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
+    if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
+    (void)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < npts; i++) {
+        int64_t f = flat_idx[i];
+        int64_t o = f % cout; f /= cout;
+        int64_t wo = f % Wo; f /= Wo;
+        int64_t ho = f % Ho; f /= Ho;
+        int64_t acc = q8_sum(x, H, Wd, cin, W, M, kh, kw, korder, stride_h, stride_w, pad_h, pad_w, f, ho, wo, o);
+        double z = (double)acc * (scale ? (double)scale[o] : 1.0);
+        if (bias) z += (double)bias[o];
+        out[i] = layer_tail(z, act);
     }
     return 0;
 }

@@ -19,7 +19,7 @@ from dataclasses import dataclass, field, replace
 
 import numpy as np
 
-F16, BF16 = 0, 1
+F16, BF16, I8 = 0, 1, 2
 K_CRS, K_RSC = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
@@ -70,6 +70,10 @@ class Layer:
 
     def algorithmic_bytes(self, sparse: bool = True) -> int:
         """x read once + y written once + weights (+ indices) + bias."""
+        if self.dtype == I8:     # int8 operands, 16-bit output, fp32 scale and bias per channel
+            xb = self.N * self.H * self.W * self.cin
+            wb = (self.cout * self.K // 2 + self.cout * self.K // 8) if sparse else self.cout * self.K
+            return xb + 2 * self.P * self.cout + wb + 8 * self.cout
         xb = 2 * self.N * self.H * self.W * self.cin
         yb = 2 * self.P * self.cout
         wb = (self.cout * self.K + self.cout * self.K // 8) if sparse else 2 * self.cout * self.K
@@ -136,6 +140,40 @@ def make_inputs(L: Layer) -> dict:
     else:
         raise ValueError(L.mask)
     return {"W": W_bits, "M": M, "x": to_bits(x, L.dtype), "bias": bias}
+
+
+def make_inputs_q8(L: Layer) -> dict:
+    """The 8-bit integer variant of a layer: (W int8 [cout,K], M, x int8 NHWC, scale fp32, bias fp32).
+
+    Draw order W, x, bias, mask logits as above; weights are the He-normal draws quantised symmetrically per output
+    channel (step = max|w| / 127), activations ReLU(N(0,1)) (or N(0,1)) quantised with one step for the tensor
+    (4 / 127, i.e. clipped at four standard deviations); `scale` is the product of the two steps, so that
+    scale * integer sum approximates the real-valued convolution."""
+    rng = np.random.Generator(np.random.PCG64(L.seed))
+    w = rng.standard_normal((L.cout, L.cin, L.kh, L.kw), dtype=np.float32) * np.float32(np.sqrt(2.0 / L.K))
+    x = rng.standard_normal((L.N, L.H, L.W, L.cin), dtype=np.float32)
+    if L.relu_input:
+        np.maximum(x, 0, out=x)
+    bias = rng.standard_normal(L.cout, dtype=np.float32) * np.float32(0.1)
+    w_step = np.abs(w).reshape(L.cout, -1).max(axis=1) / np.float32(127.0)
+    w_step = np.where(w_step > 0, w_step, np.float32(1.0)).astype(np.float32)
+    Wq = np.clip(np.rint(w / w_step[:, None, None, None]), -127, 127).astype(np.int8)
+    x_step = np.float32(4.0 / 127.0)
+    xq = np.clip(np.rint(x / x_step), -127, 127).astype(np.int8)
+    Wq = flatten_weight(Wq, L.korder)
+    if L.mask == "none":
+        M = None
+    elif L.mask == "top2":
+        mag = np.abs(Wq.astype(np.int32)).reshape(L.cout, L.K // 4, 4)
+        order = np.argsort(-mag, axis=-1, kind="stable")
+        M = np.zeros((L.cout, L.K // 4, 4), dtype=np.uint8)
+        np.put_along_axis(M, order[..., :2], 1, axis=-1)
+        M = M.reshape(L.cout, L.K)
+    elif L.mask == "logits":
+        M = mask_from_logits(rng.standard_normal((L.cout, L.K // 4, 6), dtype=np.float32))
+    else:
+        raise ValueError(L.mask)
+    return {"W": Wq, "M": M, "x": xq, "scale": (w_step * x_step).astype(np.float32), "bias": bias}
 
 
 def make_weights(L: Layer, scale: float = 1.0) -> dict:
