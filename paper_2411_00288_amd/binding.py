@@ -16,13 +16,14 @@ LIB_PATH = _HERE / "libss.so"
 
 SS_OK = 0
 SS_ERR_INVALID_ARG, SS_ERR_BAD_MASK, SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP = -1, -2, -3, -4, -5
-SS_F16, SS_BF16 = 0, 1
+SS_F16, SS_BF16, SS_I8 = 0, 1, 2
 SS_K_CRS, SS_K_RSC = 0, 1
 SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
-           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd"]
+           "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
+           "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd"]
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -62,6 +63,9 @@ def _load() -> ctypes.CDLL:
     res_args = conv_args[:7] + [vp] + conv_args[7:]          # residual after bias
     lib.ss_conv2d_res_fwd.argtypes = res_args
     lib.ss_conv2d_dense_res_fwd.argtypes = res_args
+    q8_args = [dp, vp, i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.ss_conv2d_q8_fwd.argtypes = q8_args
+    lib.ss_conv2d_q8_dense_fwd.argtypes = q8_args
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -98,10 +102,16 @@ def _dev_ptr(t, name, dtypes=None, allow_none=False):
 
 
 _T16 = (torch.float16, torch.bfloat16, torch.int16, torch.uint16)
+_T8 = (torch.int8, torch.uint8)
+
+
+def _wtypes(desc):
+    """Tensor dtypes accepted for weights of a descriptor."""
+    return _T8 if desc.dtype == SS_I8 else _T16
 
 
 def torch_dtype(dtype: int):
-    return torch.float16 if dtype == SS_F16 else torch.bfloat16
+    return {SS_F16: torch.float16, SS_BF16: torch.bfloat16, SS_I8: torch.int8}[dtype]
 
 
 def ss_packed_bytes(desc: ss_weight_desc) -> int:
@@ -131,7 +141,7 @@ def ss_mask_compress(desc: ss_weight_desc, W: torch.Tensor, M: torch.Tensor, pac
     elif packed.numel() * packed.element_size() < ss_packed_bytes(desc):
         raise SSError(SS_ERR_INVALID_ARG, "ss_mask_compress: packed buffer too small")
     bad = (ctypes.c_int32 * 2)(-1, -1)
-    st = _lib.ss_mask_compress(ctypes.byref(desc), _dev_ptr(W, "W", _T16), _dev_ptr(M, "M", (torch.uint8, torch.bool)),
+    st = _lib.ss_mask_compress(ctypes.byref(desc), _dev_ptr(W, "W", _wtypes(desc)), _dev_ptr(M, "M", (torch.uint8, torch.bool)),
                                _dev_ptr(packed, "packed"), bad, _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_mask_compress", detail=(bad[0], bad[1]) if st == SS_ERR_BAD_MASK else None)
@@ -163,7 +173,7 @@ def ss_mask_decompress(desc: ss_weight_desc, packed: torch.Tensor, out: torch.Te
     K = desc.cin * desc.kh * desc.kw
     if out is None:
         out = torch.empty((desc.cout, K), dtype=torch_dtype(desc.dtype), device=packed.device)
-    st = _lib.ss_mask_decompress(ctypes.byref(desc), _dev_ptr(packed, "packed"), _dev_ptr(out, "out", _T16),
+    st = _lib.ss_mask_decompress(ctypes.byref(desc), _dev_ptr(packed, "packed"), _dev_ptr(out, "out", _wtypes(desc)),
                                  _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_mask_decompress")
@@ -179,7 +189,7 @@ def ss_dense_pack(desc: ss_weight_desc, W: torch.Tensor, M: torch.Tensor | None,
         dense = torch.empty(ss_dense_bytes(desc), dtype=torch.uint8, device=W.device)
     elif dense.numel() * dense.element_size() < ss_dense_bytes(desc):
         raise SSError(SS_ERR_INVALID_ARG, "ss_dense_pack: dense buffer too small")
-    st = _lib.ss_dense_pack(ctypes.byref(desc), _dev_ptr(W, "W", _T16),
+    st = _lib.ss_dense_pack(ctypes.byref(desc), _dev_ptr(W, "W", _wtypes(desc)),
                             _dev_ptr(M, "M", (torch.uint8, torch.bool), allow_none=True),
                             _dev_ptr(dense, "dense"), _stream_ptr(stream))
     if st != SS_OK:
@@ -284,6 +294,64 @@ def ss_conv2d_dense_res_fwd(desc, x, dense, bias=None, residual=None, stride=(1,
     """The dense-MFMA twin of ss_conv2d_res_fwd."""
     return _conv(_lib.ss_conv2d_dense_res_fwd, "ss_conv2d_dense_res_fwd", desc, x, dense, bias, stride, pad, act, y,
                  workspace, stream, residual, True)
+
+
+def _q8_args(what, desc, x, wbuf, scale, bias, stride, pad, act, y, workspace):
+    if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
+    N, H, W, _ = x.shape
+    shp = out_shape(desc, N, H, W, stride, pad)
+    if shp[1] <= 0 or shp[2] <= 0:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")
+    if y is None:
+        y = torch.empty(shp, dtype=torch.float16, device=x.device)
+    elif tuple(y.shape) != shp or y.dtype != torch.float16:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: y must be {shp} float16")
+    need = ss_conv2d_workspace_bytes(desc, N, H, W, stride, pad)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        ws_bytes = need
+    args = (ctypes.byref(desc), _dev_ptr(x, "x", (torch.int8,)), N, H, W, _dev_ptr(wbuf, "weights"),
+            _dev_ptr(scale, "scale", (torch.float32,), allow_none=True),
+            _dev_ptr(bias, "bias", (torch.float32,), allow_none=True), stride[0], stride[1], pad[0], pad[1], act,
+            SS_F16, _dev_ptr(y, "y"), _dev_ptr(workspace, "workspace", allow_none=True), ws_bytes)
+    return args, y, workspace
+
+
+def prepare_conv2d_q8(desc, x, wbuf, scale=None, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
+                      workspace=None, sparse=True):
+    """prepare_conv2d for the 8-bit integer entry points: returns (launch, y)."""
+    what = "ss_conv2d_q8_fwd" if sparse else "ss_conv2d_q8_dense_fwd"
+    fn = getattr(_lib, what)
+    args, y, ws = _q8_args(what, desc, x, wbuf, scale, bias, stride, pad, act, y, workspace)
+    keep = (desc, x, wbuf, scale, bias, y, ws)
+
+    def launch(_keep=keep):
+        st = fn(*args, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != SS_OK:
+            raise SSError(st, what)
+    return launch, y
+
+
+def ss_conv2d_q8_fwd(desc, x, packed, scale=None, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
+                     workspace=None, stream=None) -> torch.Tensor:
+    """2:4-sparse convolution on int8 operands: x NHWC int8 -> y NHWC float16 = act(scale * sum + bias)."""
+    args, y, _ws = _q8_args("ss_conv2d_q8_fwd", desc, x, packed, scale, bias, stride, pad, act, y, workspace)
+    st = _lib.ss_conv2d_q8_fwd(*args, _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_conv2d_q8_fwd")
+    return y
+
+
+def ss_conv2d_q8_dense_fwd(desc, x, dense, scale=None, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
+                           workspace=None, stream=None) -> torch.Tensor:
+    """The dense integer-MFMA twin of ss_conv2d_q8_fwd."""
+    args, y, _ws = _q8_args("ss_conv2d_q8_dense_fwd", desc, x, dense, scale, bias, stride, pad, act, y, workspace)
+    st = _lib.ss_conv2d_q8_dense_fwd(*args, _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_conv2d_q8_dense_fwd")
+    return y
 
 
 def ss_maxpool2d(x: torch.Tensor, k: int = 3, stride: int = 2, pad: int = 1, y: torch.Tensor | None = None,

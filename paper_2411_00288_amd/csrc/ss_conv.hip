@@ -20,6 +20,7 @@
 // buffer's size and the hardware returns 0 -- no branches, no selects.
 #include "ss_internal.h"
 #include <cstdlib>
+#include <type_traits>
 
 namespace ss {
 
@@ -29,8 +30,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
 
-struct B32 {   // one lane's B fragment for a 32-wide reduction step: 16 x 16-bit
+// Accumulators of one 32x32 tile: fp32 for the 16-bit floats, int32 (exact) for 8-bit integers.
+template <int DT> using Acc = typename std::conditional<DT == SS_I8, i32x16, f32x16>::type;
+// Type of the 16-bit output (and of a residual): the operands' own, or binary16 for integer operands.
+template <int DT> constexpr int out_type() { return DT == SS_I8 ? SS_F16 : DT; }
+
+struct B32 {   // one lane's B fragment for a reduction step: 32 bytes (16 x 16-bit, or 32 x int8)
     u32x4 lo, hi;
 };
 
@@ -39,6 +48,7 @@ struct ConvParams {
     const uint8_t *a_vals;    // first value tile (after the header)
     const uint32_t *a_meta;   // first metadata tile (sparse only)
     const float *bias;
+    const float *scale;       // integer operands: per-output-channel factor of the int32 sum, or nullptr (= 1)
     const uint16_t *residual; // [P][Cout] like y, or nullptr
     uint16_t *y;
     int N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, Ho, Wo, P, K, Ks, Kp, Mt, act, korder;
@@ -65,10 +75,15 @@ __device__ __forceinline__ int fast_div(int n, unsigned mul, unsigned sh)
 constexpr unsigned kOutOfRange = 0x80000000u;   // >= any buffer size used here: the load returns 0
 constexpr int kRsrcFlags = 0x00020000;          // raw buffer, 32-bit data format (gfx9 family)
 
+// The 8-bit integer instruction (32x32x64) pairs slot s of A lane l (16 kept bytes, index field s of a full index
+// word) with bytes 16*(l/32) + 4*((s%8)/2) + idx of the B lane of the same column in lane group s/8; B lane
+// l holds the 32 reduction indices 32*(l/32) + [0,32) of pixel l%32.  Accumulators are laid out as above.
 template <int DT>
-__device__ __forceinline__ f32x16 mma_sparse(u32x4 a, const B32 &b, f32x16 c, uint32_t idx)
+__device__ __forceinline__ Acc<DT> mma_sparse(u32x4 a, const B32 &b, Acc<DT> c, uint32_t idx)
 {
-    if constexpr (DT == SS_F16)
+    if constexpr (DT == SS_I8)
+        return __builtin_amdgcn_smfmac_i32_32x32x64_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x8, b), c, (int)idx, 0, 0);
+    else if constexpr (DT == SS_F16)
         return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x16, b), c,
                                                          (int)idx, 0, 0);
     else
@@ -77,9 +92,11 @@ __device__ __forceinline__ f32x16 mma_sparse(u32x4 a, const B32 &b, f32x16 c, ui
 }
 
 template <int DT>
-__device__ __forceinline__ f32x16 mma_dense(u32x4 a, u32x4 b, f32x16 c)
+__device__ __forceinline__ Acc<DT> mma_dense(u32x4 a, u32x4 b, Acc<DT> c)
 {
-    if constexpr (DT == SS_F16)
+    if constexpr (DT == SS_I8)      // 32x32x32: A lane l slot s <-> k = 16*(l/32) + s, B likewise
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b), c, 0, 0, 0);
+    else if constexpr (DT == SS_F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -205,6 +222,9 @@ void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
     static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
+    constexpr bool Q8 = DT == SS_I8;                      // 8-bit integer operands: staged as byte pairs, int32 sums
+    constexpr int ODT = out_type<DT>();
+    static_assert(!Q8 || MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2, "byte pairs travel in 16-byte runs only");
     constexpr int NMATH = WAVES_M * WAVES_N * 64;         // threads that multiply
     constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
@@ -249,17 +269,20 @@ void conv_kernel(ConvParams p)
 
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
-    const bool with_res = p.residual != nullptr;     // uniform
+    const bool with_res = !Q8 && p.residual != nullptr;     // uniform
     float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) +
                                               (with_res ? smem_body<BM, BN, MODE, KH, KW, DEEP>(true) : smem_body<BM, BN, MODE, KH, KW, DEEP>(false)));
     // (Loaded after the first activation / weight loads are on their way: issued first, its latency would
     // sit in front of everything else.)
-    float bias_r[(BM + NMATH - 1) / NMATH];
+    float *scale_s = bias_s + BM;                     // (integer operands only)
+    float bias_r[(BM + NMATH - 1) / NMATH], scale_r[Q8 ? (BM + NMATH - 1) / NMATH : 1];
     auto load_bias = [&]() {
 #pragma unroll
         for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++) {
             const int o = m0 + tid + j * NMATH;
-            bias_r[j] = (p.bias != nullptr && tid + j * NMATH < BM && o < p.Cout) ? p.bias[o] : 0.f;
+            const bool in = tid + j * NMATH < BM && o < p.Cout;
+            bias_r[j] = (p.bias != nullptr && in) ? p.bias[o] : 0.f;
+            if constexpr (Q8) scale_r[j] = (p.scale != nullptr && in) ? p.scale[o] : 1.f;
         }
     };
 
@@ -467,7 +490,7 @@ void conv_kernel(ConvParams p)
                 a.v[0][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 1024, 0);
                 // The index word of the step pair; the step's half is shifted down where it is used, steps later (a
                 // shift here would have to wait for the load it follows and stall the wave at every step).
-                a.idx[tm] = __builtin_amdgcn_raw_buffer_load_b32(rm, (int)m_voff[tm], (ks >> 1) * 256, 0);
+                a.idx[tm] = __builtin_amdgcn_raw_buffer_load_b32(rm, (int)m_voff[tm], (Q8 ? ks : (ks >> 1)) * 256, 0);
             } else {
                 a.v[0][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 2048, 0);
                 a.v[1][tm] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)a_voff[tm], ks * 2048 + 1024, 0);
@@ -475,13 +498,13 @@ void conv_kernel(ConvParams p)
         }
     };
 
-    f32x16 acc[TM][TN];
+    Acc<DT> acc[TM][TN];
 #pragma unroll
     for (int tm = 0; tm < TM; tm++)
 #pragma unroll
         for (int tn = 0; tn < TN; tn++)
 #pragma unroll
-            for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0.f;
+            for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0;
 
     // ------------------------------------------------------------------ main loop (double-buffered LDS, ring of weight steps)
     const int nchunks = (p.Ks + KSTEPS - 1) / KSTEPS;
@@ -533,7 +556,10 @@ void conv_kernel(ConvParams p)
     if constexpr (!SPEC) stage_store(Bs0);
 #pragma unroll
     for (int j = 0; j < (BM + NMATH - 1) / NMATH; j++)
-        if (tid + j * NMATH < BM) bias_s[tid + j * NMATH] = bias_r[j];
+        if (tid + j * NMATH < BM) {
+            bias_s[tid + j * NMATH] = bias_r[j];
+            if constexpr (Q8) scale_s[tid + j * NMATH] = scale_r[j];
+        }
     __syncthreads();
     for (int c0 = 0; c0 < nchunks; c0 += UNROLL) {
 #pragma unroll
@@ -569,7 +595,8 @@ void conv_kernel(ConvParams p)
                 // (steps past the reduction length multiply clamped weights with all-zero activations:
                 // cheaper than a branch, which would force copies of every accumulator)
                 const AStep<SPARSE, TM> &as = a[g % RING];
-                const int idx_shift = (min(ci * KSTEPS + s, p.Ks - 1) & 1) * 16;      // the instruction reads index bits [15:0]
+                // the 16-bit instruction reads index bits [15:0]; the 8-bit one the whole word
+                const int idx_shift = Q8 ? 0 : (min(ci * KSTEPS + s, p.Ks - 1) & 1) * 16;
 #pragma unroll
                 for (int tm = 0; tm < TM; tm++)
 #pragma unroll
@@ -630,13 +657,21 @@ void conv_kernel(ConvParams p)
                     const int ol = (wm * TM + tm) * 32 + 8 * q + 4 * (lane >> 5);    // first of 4 consecutive output channels (tile-local)
                     const float4 bq = *reinterpret_cast<const float4 *>(bias_s + ol);
                     const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
+                    float sv[4] = {1.f, 1.f, 1.f, 1.f};
+                    if constexpr (Q8) {
+                        const float4 sq = *reinterpret_cast<const float4 *>(scale_s + ol);
+                        sv[0] = sq.x; sv[1] = sq.y; sv[2] = sq.z; sv[3] = sq.w;
+                    }
 #pragma unroll
                     for (int tn = 0; tn < TN; tn++) {
                         float r[4];
 #pragma unroll
-                        for (int e = 0; e < 4; e++) r[e] = actf(acc[tm][tn][4 * q + e] + bv[e]);
+                        for (int e = 0; e < 4; e++) {
+                            if constexpr (Q8) r[e] = actf((float)acc[tm][tn][4 * q + e] * sv[e] + bv[e]);
+                            else r[e] = actf(acc[tm][tn][4 * q + e] + bv[e]);
+                        }
                         const int pl = (wn * TN + tn) * 32 + (lane & 31);
-                        *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
+                        *reinterpret_cast<uint2 *>(Cs + pl * CROW + ol) = make_uint2(cvt_pack2<ODT>(r[0], r[1]), cvt_pack2<ODT>(r[2], r[3]));
                     }
                 }
             }
@@ -661,7 +696,7 @@ void conv_kernel(ConvParams p)
                     if (o + e < p.Cout) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
             }
         }
-    } else {
+    } else if constexpr (!Q8) {
         // With a residual the tile crosses LDS in fp32 (conv + bias); the thread that stores a 16-byte run adds the
         // residual's run (fetched before the tile is written, so its latency hides behind the LDS phase), applies
         // the activation and rounds once.
@@ -693,8 +728,8 @@ void conv_kernel(ConvParams p)
                     for (int tn = 0; tn < TN; tn++) {
                         const int pl = (wn * TN + tn) * 32 + (lane & 31);
                         *reinterpret_cast<float4 *>(Cf + pl * CROW + ol) =
-                            make_float4(acc[tm][tn][4 * q + 0] + bq.x, acc[tm][tn][4 * q + 1] + bq.y,
-                                        acc[tm][tn][4 * q + 2] + bq.z, acc[tm][tn][4 * q + 3] + bq.w);
+                            make_float4((float)acc[tm][tn][4 * q + 0] + bq.x, (float)acc[tm][tn][4 * q + 1] + bq.y,
+                                        (float)acc[tm][tn][4 * q + 2] + bq.z, (float)acc[tm][tn][4 * q + 3] + bq.w);
                     }
                 }
             }
@@ -716,14 +751,14 @@ void conv_kernel(ConvParams p)
                     uint32_t w[4];
 #pragma unroll
                     for (int e = 0; e < 4; e++)
-                        w[e] = cvt_pack2<DT>(actf(v[2 * e] + widen<DT>((uint16_t)(res[j][e] & 0xFFFFu))),
-                                             actf(v[2 * e + 1] + widen<DT>((uint16_t)(res[j][e] >> 16))));
+                        w[e] = cvt_pack2<ODT>(actf(v[2 * e] + widen<ODT>((uint16_t)(res[j][e] & 0xFFFFu))),
+                                              actf(v[2 * e + 1] + widen<ODT>((uint16_t)(res[j][e] >> 16))));
                     *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
                 } else {
                     const uint16_t *rs = p.residual + (size_t)pg * p.Cout + o;
 #pragma unroll
                     for (int e = 0; e < 8; e++)
-                        if (o + e < p.Cout) dst[e] = (uint16_t)(cvt_pack2<DT>(actf(v[e] + widen<DT>(rs[e])), 0.f) & 0xFFFFu);
+                        if (o + e < p.Cout) dst[e] = (uint16_t)(cvt_pack2<ODT>(actf(v[e] + widen<ODT>(rs[e])), 0.f) & 0xFFFFu);
                 }
             }
         };
@@ -738,8 +773,9 @@ template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MOD
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr size_t smem_plain = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(false);
-    constexpr size_t smem_res = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
+    constexpr size_t scale_bytes = DT == SS_I8 ? (size_t)BM * 4 : 0;      // the per-channel scales sit behind the bias values
+    constexpr size_t smem_plain = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(false) + scale_bytes;
+    constexpr size_t smem_res = DT == SS_I8 ? smem_plain : smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
     static_assert(smem_plain <= 160 * 1024 && smem_res <= 160 * 1024, "LDS tile too large");
     const size_t smem = p0.residual ? smem_res : smem_plain;
     ConvParams p = p0;
@@ -823,6 +859,10 @@ template <int DT, bool SPARSE>
 static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_t s)
 {
     const int taps = desc->kh * desc->kw;
+    if constexpr (DT == SS_I8) {    // validated by the entry point: byte pairs are contiguous in every 16-byte run
+        if (taps == 1) return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
+        return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
+    } else {
     // channels contiguous inside every aligned run of 8 reduction indices?
     if (desc->cin % 8 == 0 && taps == 1)
         return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
@@ -832,17 +872,28 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
         if (desc->kh == 2 && desc->kw == 2) return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);
     }
     return pick_tile<DT, SPARSE, MODE_GATHER, 1, 1>(p, s);
+    }
 }
 
+// q8: the call came through an 8-bit integer entry point (then `scale` may be given and the descriptor must say
+// SS_I8); the 16-bit entry points reject SS_I8 descriptors.
 template <bool SPARSE>
 static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd, const void *wbuf,
                       const float *bias, const void *residual, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
-                      int32_t act, void *y, void *workspace, size_t ws_bytes, void *stream)
+                      int32_t act, void *y, void *workspace, size_t ws_bytes, void *stream, bool q8 = false,
+                      const float *scale = nullptr)
 {
     (void)workspace;
     (void)ws_bytes;
     int st = check_desc(desc, SPARSE);
     if (st != SS_OK) return st;
+    if ((desc->dtype == SS_I8) != q8) return q8 ? SS_ERR_INVALID_ARG : SS_ERR_UNSUPPORTED;
+    const int esize = q8 ? 1 : 2;      // bytes per activation / weight element
+    if (q8) {
+        if (desc->cin % 16 != 0 || (desc->korder != SS_K_RSC && desc->kh * desc->kw != 1)) return SS_ERR_UNSUPPORTED;
+        if ((long long)desc->cin * desc->kh * desc->kw > 131071) return SS_ERR_UNSUPPORTED;      // int32 sums
+        if (scale && !aligned(scale, 4)) return SS_ERR_INVALID_ARG;
+    }
     if (!x || !wbuf || !y) return SS_ERR_INVALID_ARG;
     if (N <= 0 || H <= 0 || Wd <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return SS_ERR_INVALID_ARG;
     if (act != SS_ACT_NONE && act != SS_ACT_RELU && act != SS_ACT_GELU) return SS_ERR_INVALID_ARG;
@@ -854,11 +905,11 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     int Wo = (Wd + 2 * pw - desc->kw) / sw + 1;
     if (Ho <= 0 || Wo <= 0) return SS_ERR_INVALID_ARG;
     long long P = (long long)N * Ho * Wo;
-    long long xbytes = (long long)N * H * Wd * desc->cin * 2;
+    long long xbytes = (long long)N * H * Wd * desc->cin * esize;
     long long yelems = P * desc->cout;
     // 32-bit byte offsets inside the kernel; "out of range" must stay above every real offset
     if (xbytes >= (1ll << 31) - (1ll << 26) || yelems >= (1ll << 31) || P >= (1ll << 31) - 512) return SS_ERR_UNSUPPORTED;
-    if ((long long)(ph + desc->kh + 1) * (Wd + pw + desc->kw) * desc->cin * 2 >= (1ll << 26)) return SS_ERR_UNSUPPORTED;
+    if ((long long)(ph + desc->kh + 1) * (Wd + pw + desc->kw) * desc->cin * esize >= (1ll << 26)) return SS_ERR_UNSUPPORTED;
 
     TileDims t = tile_dims(desc);
     size_t wbytes = SPARSE ? packed_size(t) : dense_size(t);
@@ -868,11 +919,13 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.a_vals = static_cast<const uint8_t *>(wbuf) + kHeaderBytes;
     p.a_meta = reinterpret_cast<const uint32_t *>(p.a_vals + (size_t)t.Mt * t.Ks * 1024);
     p.bias = bias;
+    p.scale = scale;
     p.residual = static_cast<const uint16_t *>(residual);
     p.y = static_cast<uint16_t *>(y);
-    p.N = N; p.H = H; p.W = Wd; p.Cin = desc->cin; p.Cout = desc->cout; p.kh = desc->kh; p.kw = desc->kw;
+    // The kernel stages 2-byte units: for 8-bit operands a unit is a pair of channels, and Cin and K count pairs.
+    p.N = N; p.H = H; p.W = Wd; p.Cin = desc->cin / (q8 ? 2 : 1); p.Cout = desc->cout; p.kh = desc->kh; p.kw = desc->kw;
     p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.Ho = Ho; p.Wo = Wo; p.P = (int)P;
-    p.K = t.K; p.Ks = t.Ks; p.Kp = t.Kp; p.Mt = t.Mt; p.act = act; p.korder = desc->korder;
+    p.K = t.K / (q8 ? 2 : 1); p.Ks = t.Ks; p.Kp = t.Kp; p.Mt = t.Mt; p.act = act; p.korder = desc->korder;
     p.tiles_m = 0;
     p.tm_mul = p.tm_sh = 0;
     fast_div_setup((unsigned)(Ho * Wo), &p.howo_mul, &p.howo_sh);
@@ -881,6 +934,7 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.a_bytes = (unsigned)((size_t)t.Mt * t.Ks * (SPARSE ? 1024 : 2048));
     p.meta_bytes = SPARSE ? (unsigned)((size_t)t.Mt * t.Kp * 256) : 4u;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (q8) return pick_mode<SS_I8, SPARSE>(desc, p, s);
     return desc->dtype == SS_F16 ? pick_mode<SS_F16, SPARSE>(desc, p, s) : pick_mode<SS_BF16, SPARSE>(desc, p, s);
 }
 
@@ -932,4 +986,24 @@ extern "C" int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x
 {
     return conv_entry<false>(desc, x, N, H, Wd, dense, bias, residual, stride_h, stride_w, pad_h, pad_w, act, y,
                              workspace, ws_bytes, stream);
+}
+
+extern "C" int ss_conv2d_q8_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                const void *packed, const float *scale, const float *bias, int32_t stride_h,
+                                int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act, int32_t out_dtype, void *y,
+                                void *workspace, size_t ws_bytes, void *stream)
+{
+    if (out_dtype != SS_F16) return out_dtype == SS_BF16 ? SS_ERR_UNSUPPORTED : SS_ERR_INVALID_ARG;
+    return conv_entry<true>(desc, x, N, H, Wd, packed, bias, nullptr, stride_h, stride_w, pad_h, pad_w, act, y,
+                            workspace, ws_bytes, stream, true, scale);
+}
+
+extern "C" int ss_conv2d_q8_dense_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                      const void *dense, const float *scale, const float *bias, int32_t stride_h,
+                                      int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act, int32_t out_dtype,
+                                      void *y, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (out_dtype != SS_F16) return out_dtype == SS_BF16 ? SS_ERR_UNSUPPORTED : SS_ERR_INVALID_ARG;
+    return conv_entry<false>(desc, x, N, H, Wd, dense, bias, nullptr, stride_h, stride_w, pad_h, pad_w, act, y,
+                             workspace, ws_bytes, stream, true, scale);
 }

@@ -165,6 +165,107 @@ __global__ __launch_bounds__(256) void dense_pack_kernel(const uint16_t *__restr
     *reinterpret_cast<uint4 *>(dense + kHeaderBytes + ((size_t)tile * 64 + lane) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// ---------------------------------------------------------------------------------------------
+// 8-bit integer operands.  One thread produces one lane of one value tile: 16 packed bytes and the 32 index
+// bits that go with them.  Lane l of tile (mt, ks) owns row 32*mt + l%32 and, in slots 2j, 2j+1 (j = 0..7),
+// block 16*ks + 8*(j/4) + 4*(l/32) + j%4: gfx950's 32x32x64 integer sparse MFMA pairs slot s of lane l with the
+// bytes 16*(l/32) + 4*((s%8)/2) + [0,4) of the B lane of the same column in lane group s/8, and B lane groups
+// hold the reduction indices 64*ks + 32*group + [0,32).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void compress8_kernel(const uint8_t *__restrict__ W, const uint8_t *__restrict__ M,
+                                                        uint8_t *__restrict__ packed, int cout, int K, int Mt, int Ks)
+{
+    int tid = blockIdx.x * 256 + threadIdx.x;
+    int total = Mt * Ks * 64;
+    if (tid >= total) return;
+    int lane = tid & 63;
+    int tile = tid >> 6;
+    int ks = tile % Ks;
+    int mt = tile / Ks;
+    int row = mt * 32 + (lane & 31);
+    int ga = lane >> 5;
+    int G = K >> 2;
+
+    uint32_t v[4] = {0, 0, 0, 0};
+    uint32_t nibbles = 0;
+    uint32_t *first_bad = reinterpret_cast<uint32_t *>(packed) + kHdrFirstBad;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        int g = 16 * ks + 8 * (j >> 2) + 4 * ga + (j & 3);
+        uint32_t pair = 0, nib = 0x4;
+        if (row < cout && g < G) {
+            size_t e = (size_t)row * K + 4 * (size_t)g;
+            uint32_t m = *reinterpret_cast<const uint32_t *>(M + e);
+            uint32_t w = *reinterpret_cast<const uint32_t *>(W + e);
+            bool ok = ((m & 0xFEFEFEFEu) == 0) && (__popc(m) == 2);
+            if (ok) {
+                int i0 = (__ffs(m) - 1) >> 3;
+                int i1 = (31 - __clz(m)) >> 3;
+                pair = ((w >> (8 * i0)) & 0xFFu) | (((w >> (8 * i1)) & 0xFFu) << 8);
+                nib = (uint32_t)(i0 | (i1 << 2));
+            } else {
+                atomicMin(first_bad, (uint32_t)((size_t)row * G + g));
+            }
+        }
+        v[j >> 1] |= pair << (16 * (j & 1));
+        nibbles |= nib << (4 * j);
+    }
+    *reinterpret_cast<uint4 *>(packed + kHeaderBytes + ((size_t)tile * 64 + lane) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
+    uint32_t *meta = reinterpret_cast<uint32_t *>(packed + kHeaderBytes + (size_t)Mt * Ks * 1024);
+    meta[(size_t)tile * 64 + lane] = nibbles;
+}
+
+// thread per (row, block): inverse permutation, writes 4 bytes
+__global__ __launch_bounds__(256) void decompress8_kernel(const uint8_t *__restrict__ packed, uint8_t *__restrict__ Wm,
+                                                          int cout, int K, int Mt, int Ks)
+{
+    int G = K >> 2;
+    int tid = blockIdx.x * 256 + threadIdx.x;
+    if (tid >= cout * G) return;
+    int g = tid % G, row = tid / G;
+    int mt = row >> 5, i = row & 31;
+    int ks = g >> 4, gl = g & 15;
+    int ga = (gl >> 2) & 1;
+    int j = 4 * (gl >> 3) + (gl & 3);
+    int lane = 32 * ga + i;
+    const uint16_t *vals = reinterpret_cast<const uint16_t *>(packed + kHeaderBytes);
+    uint32_t pair = vals[(((size_t)mt * Ks + ks) * 64 + lane) * 8 + j];
+    const uint32_t *meta = reinterpret_cast<const uint32_t *>(packed + kHeaderBytes + (size_t)Mt * Ks * 1024);
+    uint32_t nib = (meta[((size_t)mt * Ks + ks) * 64 + lane] >> (4 * j)) & 0xFu;
+    int i0 = nib & 3, i1 = (nib >> 2) & 3;
+    uint32_t w = ((pair & 0xFFu) << (8 * i0)) | ((pair >> 8) << (8 * i1));
+    *reinterpret_cast<uint32_t *>(Wm + (size_t)row * K + 4 * (size_t)g) = w;
+}
+
+// Dense twin operand: thread per (tile (mt, ks, h), lane); 16 bytes k = 64*ks + 32*(l/32) + 16*h + s.
+__global__ __launch_bounds__(256) void dense_pack8_kernel(const uint8_t *__restrict__ W, const uint8_t *__restrict__ M,
+                                                          uint8_t *__restrict__ dense, int cout, int K, int Mt, int Ks)
+{
+    int tid = blockIdx.x * 256 + threadIdx.x;
+    int total = Mt * Ks * 2 * 64;
+    if (tid >= total) return;
+    int lane = tid & 63;
+    int tile = tid >> 6;
+    int h = tile & 1;
+    int ks = (tile >> 1) % Ks;
+    int mt = (tile >> 1) / Ks;
+    int row = mt * 32 + (lane & 31);
+    int kbase = 64 * ks + 32 * (lane >> 5) + 16 * h;
+    uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < 16; s++) {
+        int k = kbase + s;
+        uint32_t val = 0;
+        if (row < cout && k < K) {
+            size_t e = (size_t)row * K + k;
+            bool keep = (M == nullptr) || (M[e] != 0);
+            val = keep ? (uint32_t)W[e] : 0u;
+        }
+        o[s >> 2] |= val << (8 * (s & 3));
+    }
+    *reinterpret_cast<uint4 *>(dense + kHeaderBytes + ((size_t)tile * 64 + lane) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 }  // namespace ss
 
 using namespace ss;
@@ -206,7 +307,9 @@ static int compress_entry(const ss_weight_desc *desc, void *W, const void *U, co
     int st = check_desc(desc, true);
     if (st != SS_OK) return st;
     if (!W || !M || !packed) return SS_ERR_INVALID_ARG;
-    if (!aligned(W, 8) || !aligned(M, 4) || !aligned(packed, 16) || (U && !aligned(U, 8))) return SS_ERR_INVALID_ARG;
+    const bool i8 = desc->dtype == SS_I8;
+    if (i8 && U) return SS_ERR_UNSUPPORTED;       // the update is defined on the 16-bit floats only
+    if (!aligned(W, i8 ? 4 : 8) || !aligned(M, 4) || !aligned(packed, 16) || (U && !aligned(U, 8))) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *p = static_cast<uint8_t *>(packed);
@@ -216,7 +319,9 @@ static int compress_entry(const ss_weight_desc *desc, void *W, const void *U, co
     dim3 grid((total + 255) / 256), block(256);
     uint16_t *w = static_cast<uint16_t *>(W);
     const uint16_t *u = static_cast<const uint16_t *>(U);
-    if (!U)
+    if (i8)
+        compress8_kernel<<<grid, block, 0, s>>>(static_cast<const uint8_t *>(W), M, p, desc->cout, t.K, t.Mt, t.Ks);
+    else if (!U)
         compress_kernel<SS_F16, false><<<grid, block, 0, s>>>(w, nullptr, M, p, desc->cout, t.K, t.Mt, t.Ks, t.Kp);
     else if (desc->dtype == SS_F16)
         compress_kernel<SS_F16, true><<<grid, block, 0, s>>>(w, u, M, p, desc->cout, t.K, t.Mt, t.Ks, t.Kp);
@@ -254,9 +359,15 @@ extern "C" int ss_mask_decompress(const ss_weight_desc *desc, const void *packed
     int st = check_desc(desc, true);
     if (st != SS_OK) return st;
     if (!packed || !W_masked_out) return SS_ERR_INVALID_ARG;
-    if (!aligned(packed, 16) || !aligned(W_masked_out, 8)) return SS_ERR_INVALID_ARG;
+    const bool i8 = desc->dtype == SS_I8;
+    if (!aligned(packed, 16) || !aligned(W_masked_out, i8 ? 4 : 8)) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
     int total = desc->cout * t.G;
+    if (i8) {
+        decompress8_kernel<<<(total + 255) / 256, 256, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const uint8_t *>(packed), static_cast<uint8_t *>(W_masked_out), desc->cout, t.K, t.Mt, t.Ks);
+        return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
+    }
     decompress_kernel<<<(total + 255) / 256, 256, 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<const uint8_t *>(packed), static_cast<uint16_t *>(W_masked_out), desc->cout, t.K, t.Mt, t.Ks, t.Kp);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
@@ -267,14 +378,18 @@ extern "C" int ss_dense_pack(const ss_weight_desc *desc, const void *W, const ui
     int st = check_desc(desc, false);
     if (st != SS_OK) return st;
     if (!W || !dense) return SS_ERR_INVALID_ARG;
-    if (!aligned(W, 2) || !aligned(dense, 16)) return SS_ERR_INVALID_ARG;
+    if (!aligned(W, desc->dtype == SS_I8 ? 1 : 2) || !aligned(dense, 16)) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *p = static_cast<uint8_t *>(dense);
     write_header_kernel<<<1, 64, 0, s>>>(reinterpret_cast<uint32_t *>(p), kMagicDense, desc->cout, desc->cin,
                                          desc->kh, desc->kw, desc->dtype, desc->korder, t.Mt, t.Ks);
     int total = t.Mt * t.Ks * 2 * 64;
-    dense_pack_kernel<<<(total + 255) / 256, 256, 0, s>>>(static_cast<const uint16_t *>(W), M, p, desc->cout, t.K,
-                                                          t.Mt, t.Ks);
+    if (desc->dtype == SS_I8)
+        dense_pack8_kernel<<<(total + 255) / 256, 256, 0, s>>>(static_cast<const uint8_t *>(W), M, p, desc->cout, t.K,
+                                                               t.Mt, t.Ks);
+    else
+        dense_pack_kernel<<<(total + 255) / 256, 256, 0, s>>>(static_cast<const uint16_t *>(W), M, p, desc->cout, t.K,
+                                                              t.Mt, t.Ks);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
 }
