@@ -26,6 +26,7 @@ sys.path.insert(0, str(ROOT))
 
 SPARSE_PEAK_TFLOPS = 5000.0   # 2:4-sparse fp16/bf16 MFMA, dense-equivalent = 2 x the 2.5 PFLOP/s dense peak
 DENSE_PEAK_TFLOPS = 2500.0
+SPARSE_INT8_PEAK_TOPS = 10000.0     # 2 x the published dense int8 peak (5.0 POP/s), dense-equivalent
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the sparse kernel on configs[1], from the rocprofv3 counter runs summarised in
 # profiles/conv_kernel_cfg1_hbm_traffic.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (factors from a streaming copy).
@@ -83,6 +84,65 @@ class LayerRun:
     def densef(self):
         self.i = (self.i + 1) % len(self.xs)
         self.calls_d[self.i]()
+
+
+class Q8Run:
+    """The 8-bit integer variant of a layer (channels-last flattening): device operands drawn on the GPU for timing
+    (int8 weights ~ N(0, 40) clipped, activations ReLU(N(0, 32)) clipped, random 2:4 patterns, per-channel scale)."""
+
+    def __init__(self, L, torch, ss, wl):
+        self.L = L
+        korder = wl.K_RSC if L.kh * L.kw > 1 else L.korder
+        self.desc = ss.make_desc(L.cout, L.cin, L.kh, L.kw, ss.SS_I8, korder)
+        g = torch.Generator(device="cuda").manual_seed(L.seed)
+        W = (torch.randn((L.cout, L.K), generator=g, device="cuda") * 40).clamp_(-127, 127).round_().to(torch.int8)
+        pat = torch.tensor([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]],
+                           dtype=torch.uint8, device="cuda")
+        M = pat[torch.randint(0, 6, (L.cout, L.K // 4), generator=g, device="cuda")].reshape(L.cout, L.K).contiguous()
+        x = torch.randn((L.N, L.H, L.W, L.cin), generator=g, device="cuda") * 32
+        x = (x.clamp_(min=0) if L.relu_input else x).clamp_(-127, 127).round_().to(torch.int8)
+        self.scale = torch.full((L.cout,), 1.0 / (40 * 32 * (L.K / 2) ** 0.5), device="cuda")
+        self.bias = torch.randn(L.cout, generator=g, device="cuda") * 0.1
+        self.packed = ss.ss_mask_compress(self.desc, W, M)
+        self.dense = ss.ss_dense_pack(self.desc, W, M)
+        st, pd = (L.stride,) * 2, (L.pad,) * 2
+        self.densef, self.y = ss.prepare_conv2d_q8(self.desc, x, self.dense, self.scale, self.bias, st, pd, L.act, sparse=False)
+        self.sparse, _ = ss.prepare_conv2d_q8(self.desc, x, self.packed, self.scale, self.bias, st, pd, L.act, y=self.y)
+        self.keep = (W, M, x)
+
+
+def q8_point(torch, ss, wl, L, steps, warmup, reps=3):
+    """Sparse / dense-twin time of the 8-bit variant of a layer and its rate in dense-equivalent TOP/s."""
+    run = Q8Run(L, torch, ss, wl)
+    ts = median_time(torch, run.sparse, steps, warmup, reps=reps)
+    td = median_time(torch, run.densef, steps, warmup, reps=reps)
+    tops = L.dense_equiv_flop / ts / 1e9
+    return {"sparse_us": ts * 1e3, "dense_twin_us": td * 1e3, "speedup": td / ts, "tops": tops,
+            "frac_sparse_int8_peak": tops / SPARSE_INT8_PEAK_TOPS}
+
+
+def print_q8_table(torch, ss, wl, steps, warmup):
+    """8-bit integer variants of the benchmark layers and of the masked ResNet-50 layers (batch 64), next to the
+    16-bit path on the same shape (channels-last flattening for both, so the comparison is like for like)."""
+    import dataclasses
+    layers = [wl.CONFIG1, wl.with_batch(wl.CONFIG1, 500), wl.with_batch(wl.CONFIG1, 512), wl.CONFIG2]
+    layers += [L for L in wl.resnet50_layers(64) if L.mask != "none" and L.cin % 16 == 0]
+    print(f"{'layer':34s} {'N':>4s} {'int8 us':>9s} {'twin us':>9s} {'x':>5s} {'TOP/s':>8s} {'16-bit us':>10s} {'int8 gain':>9s}")
+    tot8 = tot16 = totd = 0.0
+    for i, L in enumerate(layers):
+        r = q8_point(torch, ss, wl, L, steps, warmup)
+        L16 = dataclasses.replace(L, korder=wl.K_RSC if L.kh * L.kw > 1 else L.korder)
+        run16 = LayerRun(L16, torch, ss, wl, values=False)
+        t16 = median_time(torch, run16.sparse, steps, warmup, reps=3) * 1e3
+        del run16
+        print(f"{L.name:34s} {L.N:4d} {r['sparse_us']:9.1f} {r['dense_twin_us']:9.1f} {r['speedup']:5.2f} {r['tops']:8.0f} "
+              f"{t16:10.1f} {t16 / r['sparse_us']:9.2f}", flush=True)
+        if i >= 4:      # the ResNet-50 layers
+            tot8 += r["sparse_us"] * L.count
+            totd += r["dense_twin_us"] * L.count
+            tot16 += t16 * L.count
+    print(f"ResNet-50 masked layers, batch 64: int8 sparse {tot8 / 1e3:.3f} ms, int8 dense twin {totd / 1e3:.3f} ms, "
+          f"16-bit sparse {tot16 / 1e3:.3f} ms")
 
 
 def time_graph(torch, fn, steps: int, warmup: int) -> float:
@@ -267,6 +327,7 @@ def main():
     ap.add_argument("--cold", action="store_true", help="with --table: rotate buffers so activations are not cache-resident")
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
     ap.add_argument("--trunk", action="store_true", help="end-to-end ResNet-50 convolution trunk (images/s) instead of the JSON line")
+    ap.add_argument("--q8", action="store_true", help="report of the 8-bit integer precision point instead of the JSON line")
     ap.add_argument("--tail", action="store_true", help="report of the fused residual / activation tail instead of the JSON line")
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
@@ -290,6 +351,9 @@ def main():
 
     if args.trunk:
         print_trunk(torch, ss, wl)
+        return
+    if args.q8:
+        print_q8_table(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50))
         return
     if args.tail:
         print_tail_table(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50))
@@ -342,6 +406,9 @@ def main():
     te_s = median_time(torch, even.sparse, 20, 3, reps=3)
     te_d = median_time(torch, even.densef, 20, 3, reps=3)
     del even
+    # the 8-bit integer precision point on the same shape (channels-last flattening), N = 32 and N = 500
+    q8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50))
+    q8_big = q8_point(torch, ss, wl, Leven, 20, 3)
     tc = time_launches(torch, lambda: ss.ss_mask_compress(run.desc, run.W, run.M, packed=run.packed), 20, 3)
     Wu, Uz = run.W.clone(), torch.zeros_like(run.W)     # a zero update: the packed weights stay what they are
     tu = time_launches(torch, lambda: ss.ss_mask_update_compress(run.desc, Wu, Uz, run.M, packed=run.packed), 20, 3)
@@ -363,6 +430,8 @@ def main():
                                      "dense_twin_us": te_d * 1e3, "tflops": Leven.dense_equiv_flop / te_s / 1e9,
                                      "speedup": te_d / te_s,
                                      "frac_sparse_peak": Leven.dense_equiv_flop / te_s / 1e9 / SPARSE_PEAK_TFLOPS},
+        "int8": {"workload": "same shape with int8 operands (channels-last flattening), fp16 output", "n32": q8_small,
+                 "n500": q8_big, "peak_tops": SPARSE_INT8_PEAK_TOPS},
         "compress_us": tc * 1e3, "update_compress_us": tu * 1e3, "eager_launch_us": eager_ms * 1e3,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": CFG1_TRAFFIC_BYTES,

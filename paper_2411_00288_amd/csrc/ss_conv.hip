@@ -141,6 +141,7 @@ __device__ __forceinline__ float normal_cdf(float v)
 //   MODE_VEC    channels are contiguous inside every aligned run of 8 reduction indices (1x1
 //               kernels, or the channels-last flattening, with cin % 8 == 0): 16-byte loads,
 //               chunks of 64 reduction indices.
+//   MODE_VEC8   the same with chunks of 256 reduction indices, for long reductions: a quarter of the barriers.
 //   MODE_PW     MODE_VEC specialised for 1x1 kernels: a pixel's offset is fixed for the whole
 //               reduction and the chunk's channel offset travels in the load's scalar offset.
 //               Chunks of 128 reduction indices (MODE_PW) or 64 (MODE_PW2, for very short reductions).
@@ -151,7 +152,8 @@ __device__ __forceinline__ float normal_cdf(float v)
 //               KH*KW taps as 16-byte channel vectors and transposes them in registers to
 //               channel-major order before the LDS write, so the MFMA side still reads 16-byte
 //               vectors.  A chunk is 32 channels = KH*KW reduction steps.
-enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2, MODE_PW = 3, MODE_PW2 = 4 };
+enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2, MODE_PW = 3, MODE_PW2 = 4, MODE_VEC8 = 5 };
+constexpr bool is_vec(int mode) { return mode == MODE_VEC || mode == MODE_VEC8; }
 
 // Weight fragments of one 32-wide reduction step for the TM row tiles of a wave.
 template <bool SPARSE, int TM>
@@ -163,7 +165,7 @@ struct AStep {
 template <int MODE, int KH, int KW, bool DEEP>
 struct ChunkShape {
     static constexpr int TAPS = KH * KW;
-    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_PW ? 4 : 2);   // 32-wide reduction steps per LDS chunk
+    static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_VEC8 ? 8 : (MODE == MODE_PW ? 4 : 2));   // 32-wide reduction steps per LDS chunk
     static constexpr int BK = KSTEPS * 32;
     static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
     // LDS copies of the chunk: double-buffered, so that the next chunk is written while this one is
@@ -217,14 +219,14 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // wave's matrix instructions.
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC>
 __global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
-__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS))))
+__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8))))
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
     static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
     constexpr bool Q8 = DT == SS_I8;                      // 8-bit integer operands: staged as byte pairs, int32 sums
     constexpr int ODT = out_type<DT>();
-    static_assert(!Q8 || MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2, "byte pairs travel in 16-byte runs only");
+    static_assert(!Q8 || is_vec(MODE) || MODE == MODE_PW || MODE == MODE_PW2, "byte pairs travel in 16-byte runs only");
     constexpr int NMATH = WAVES_M * WAVES_N * 64;         // threads that multiply
     constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
@@ -288,7 +290,7 @@ void conv_kernel(ConvParams p)
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
-    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_PW ? 16 : 8));
+    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_VEC8 ? 32 : (MODE == MODE_PW ? 16 : 8)));
     constexpr int ST = SPEC ? (256 < BN * UNITS ? 256 : BN * UNITS) : (NT < BN * UNITS ? NT : BN * UNITS);     // staging threads (whole waves); the rest only multiply
     constexpr int ITEMS = BN * UNITS / ST;
     constexpr int NSET = SPEC ? 2 : 1;                    // producer waves hold two chunks in registers
@@ -324,7 +326,7 @@ void conv_kernel(ConvParams p)
 
     // MODE_VEC: position of this thread's 8-element run in the (tap, channel) space
     int vk = unit * 8, vc = 0, vr = 0, vt = 0;
-    if constexpr (MODE == MODE_VEC) {
+    if constexpr (is_vec(MODE)) {
         int tap = vk / p.Cin;
         vc = vk - tap * p.Cin;
         vr = tap / p.kw;
@@ -356,7 +358,7 @@ void conv_kernel(ConvParams p)
         }
     }
 
-    u32x4 stage_v_[NSET][(MODE == MODE_VEC || MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
+    u32x4 stage_v_[NSET][(is_vec(MODE) || MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
     uint16_t stage_g_[NSET][MODE == MODE_GATHER ? ITEMS : 1][4];
     u32x4 stage_t_[NSET][MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
@@ -365,7 +367,7 @@ void conv_kernel(ConvParams p)
         auto &stage_v = stage_v_[set];
         auto &stage_g = stage_g_[set];
         auto &stage_t = stage_t_[set];
-        if constexpr (MODE == MODE_VEC) {
+        if constexpr (is_vec(MODE)) {
             const unsigned koff = vk < p.K ? (unsigned)(((vr * p.W + vt) * p.Cin + vc) * 2) : kOutOfRange;
 #pragma unroll
             for (int i = 0; i < ITEMS; i++) {
@@ -829,6 +831,25 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
     return SS_ERR_INVALID_ARG;
 }
 
+// Tile id for a problem.  Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes, 256 compute
+// units).  pointwise: 1x1 staging; bigchunk: staging in chunks of 256+ reduction indices (3x3 tap transpose, long
+// channels-last reductions).
+static int choose_tile(const ConvParams &p, bool pointwise, bool bigchunk)
+{
+    if (p.Cout <= 64) {
+        const bool deep = n_blocks(p, 64, 64) <= 1024 || (pointwise && p.K >= 256);
+        return deep ? 1 : 0;
+    }
+    // Grids of at most one workgroup per compute unit: nothing else hides a wave's stalls, so separate producer
+    // waves pay.  Larger grids do better with two four-wave workgroups per compute unit.
+    const long long b128 = n_blocks(p, 128, 64), b256 = n_blocks(p, 256, 64);
+    if (p.Cout > 128 && b256 > 128 && b256 <= 256) return 5;
+    if (b128 <= 256) return 4;
+    if (p.Cout >= 512 && p.K >= 512) return 3;
+    if (bigchunk && p.Cout >= 256 && b256 >= 512) return 3;
+    return 2;
+}
+
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
@@ -838,21 +859,23 @@ static int pick_tile(const ConvParams &p, hipStream_t s)
         int st = launch_tile<DT, SPARSE, MODE, KH, KW>(forced, p, s);
         if (st != SS_ERR_INVALID_ARG) return st;
     }
-    // Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes, 256 compute units).
     constexpr bool pointwise = MODE == MODE_PW || MODE == MODE_PW2;
-    constexpr bool taps3x3 = MODE == MODE_TAPS && KH * KW > 4;
-    if (p.Cout <= 64) {
-        const bool deep = n_blocks(p, 64, 64) <= 1024 || (pointwise && p.K >= 256);
-        return launch_tile<DT, SPARSE, MODE, KH, KW>(deep ? 1 : 0, p, s);
+    constexpr bool bigchunk = (MODE == MODE_TAPS && KH * KW > 4) || MODE == MODE_VEC8;
+    return launch_tile<DT, SPARSE, MODE, KH, KW>(choose_tile(p, pointwise, bigchunk), p, s);
+}
+
+// Channels-last flattening with taps: chunks of 256 reduction indices (a quarter of the barriers, four times the
+// LDS) pay where the tile that goes with them is one of the deep ones -- few workgroups per compute unit anyway --
+// and cost occupancy on the large grids of the shallow tiles.  (The 8-bit 256x64 tile without producer waves needs
+// a few registers more than two waves per SIMD leave, so it keeps the short chunks.)
+template <int DT, bool SPARSE>
+static int pick_vec(const ConvParams &p, hipStream_t s)
+{
+    if (p.K >= 512) {
+        const int id = getenv("SS_TILE") ? atoi(getenv("SS_TILE")) : choose_tile(p, false, true);
+        if (id == 4 || id == 5 || (id == 3 && DT != SS_I8)) return pick_tile<DT, SPARSE, MODE_VEC8, 1, 1>(p, s);
     }
-    // Grids of at most one workgroup per compute unit: nothing else hides a wave's stalls, so separate producer
-    // waves pay.  Larger grids do better with two four-wave workgroups per compute unit.
-    const long long b128 = n_blocks(p, 128, 64), b256 = n_blocks(p, 256, 64);
-    if (p.Cout > 128 && b256 > 128 && b256 <= 256) return launch_tile<DT, SPARSE, MODE, KH, KW>(5, p, s);
-    if (b128 <= 256) return launch_tile<DT, SPARSE, MODE, KH, KW>(4, p, s);
-    if (p.Cout >= 512 && p.K >= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(3, p, s);
-    if (taps3x3 && p.Cout >= 256 && b256 >= 512) return launch_tile<DT, SPARSE, MODE, KH, KW>(3, p, s);
-    return launch_tile<DT, SPARSE, MODE, KH, KW>(2, p, s);
+    return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
 }
 
 template <int DT, bool SPARSE>
@@ -861,12 +884,12 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
     const int taps = desc->kh * desc->kw;
     if constexpr (DT == SS_I8) {    // validated by the entry point: byte pairs are contiguous in every 16-byte run
         if (taps == 1) return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
-        return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
+        return pick_vec<DT, SPARSE>(p, s);
     } else {
     // channels contiguous inside every aligned run of 8 reduction indices?
     if (desc->cin % 8 == 0 && taps == 1)
         return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
-    if (desc->cin % 8 == 0 && desc->korder == SS_K_RSC) return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
+    if (desc->cin % 8 == 0 && desc->korder == SS_K_RSC) return pick_vec<DT, SPARSE>(p, s);
     if (desc->korder == SS_K_CRS && desc->cin % 32 == 0) {
         if (desc->kh == 3 && desc->kw == 3) return pick_tile<DT, SPARSE, MODE_TAPS, 3, 3>(p, s);
         if (desc->kh == 2 && desc->kw == 2) return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);

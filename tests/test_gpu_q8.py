@@ -117,6 +117,7 @@ def test_compress_reports_first_invalid_block_and_rejects_updates(ss):
 
 SHAPES = [
     _L(3, 14, 14, 64, 300, 3, p=1),                 # 3x3, K = 576 bytes = 9 steps (ragged last chunk of 2), ragged rows / pixels
+    _L(2, 9, 10, 128, 200, 3, p=1, seed=4),         # K = 1152 bytes: the long-reduction staging (chunks of 512 bytes), 2.25 chunks
     _L(2, 15, 13, 96, 136, 3, s=2, p=1),            # stride 2
     _L(3, 9, 11, 160, 264, 1, korder=wl.K_CRS),     # pointwise, K = 160 (2.5 steps)
     _L(2, 10, 10, 64, 130, 1),                      # pointwise, a single step (short-reduction staging)
@@ -149,7 +150,7 @@ def force_tile():
 
 
 @pytest.mark.parametrize("tile", TILE_IDS)
-@pytest.mark.parametrize("L", SHAPES[:5], ids=lambda L: L.name)
+@pytest.mark.parametrize("L", SHAPES[:6], ids=lambda L: L.name)
 def test_every_tile_shape_matches_oracle(ss, force_tile, L, tile):
     d = wl.make_inputs_q8(L)
     ref = _ref(L, d)

@@ -30,6 +30,7 @@ SHAPES = [
     _L(2, 10, 10, 64, 130, 1),                             # pointwise, short reduction (2 steps)
     _L(2, 12, 12, 96, 200, 2, s=2),                        # 2x2 stride 2 tap transpose
     _L(2, 9, 9, 24, 140, 3, p=1, korder=wl.K_RSC),         # channels-last flattening with taps
+    _L(2, 9, 9, 64, 140, 3, p=1, korder=wl.K_RSC, seed=5), # channels-last flattening, K = 576: chunks of 256 (2.25 of them)
     _L(1, 11, 9, 12, 150, 3, p=1),                         # gather fallback (cin % 32 != 0)
     _L(2, 14, 14, 192, 260, 3, p=1, seed=3),               # six chunks of 32 channels
 ]
