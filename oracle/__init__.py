@@ -21,7 +21,7 @@ _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "ss_oracle.c"
 _LIB = _HERE / "libss_oracle.so"
 
-F16, BF16, I8 = 0, 1, 2
+F16, BF16, I8, F8 = 0, 1, 2, 3
 K_CRS, K_RSC = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
@@ -79,6 +79,12 @@ def _load():
         lib.ss_oracle_conv2d_q8_points.restype = ctypes.c_int
         lib.ss_oracle_conv2d_q8_points.argtypes = [p, i64, i64, i64, i64, p, p, i64, i64, i64, ctypes.c_int, p, p,
                                                    i64, i64, i64, i64, ctypes.c_int, p, i64, p]
+        lib.ss_oracle_e4m3_to_double.restype = ctypes.c_double
+        lib.ss_oracle_e4m3_to_double.argtypes = [ctypes.c_uint8]
+        for fn in (lib.ss_oracle_conv2d_f8, lib.ss_oracle_conv2d_f8_points):
+            fn.restype = ctypes.c_int
+        lib.ss_oracle_conv2d_f8.argtypes = lib.ss_oracle_conv2d_q8.argtypes
+        lib.ss_oracle_conv2d_f8_points.argtypes = lib.ss_oracle_conv2d_q8_points.argtypes
         _lib = lib
     return _lib
 
@@ -312,4 +318,64 @@ def conv2d_q8_points(x_q, W_q, M, flat_idx, *, cin, kh, kw, korder=K_CRS, scale=
                                             _ptr(flat_idx), flat_idx.size, _ptr(out))
     if st:
         raise ValueError(f"oracle conv2d_q8_points failed (status {st})")
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# 8-bit float (OCP FP8 E4M3) precision point.  The structured representation of FP8 weights is the byte one above
+# (compress8 / decompress8 on the bytes viewed as int8).
+# ---------------------------------------------------------------------------------------------
+def e4m3_to_double(b) -> np.ndarray:
+    """Exact value of every E4M3 byte (NaN for 0x7F / 0xFF)."""
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    lib = _load()
+    table = np.array([lib.ss_oracle_e4m3_to_double(i) for i in range(256)], dtype=np.float64)
+    return table[b]
+
+
+def _f8_args(x_b, W_b, M, scale, bias, cin, kh, kw):
+    x_b, W_b = _c(x_b, np.uint8), _c(W_b, np.uint8)
+    N, H, Wd, c = x_b.shape
+    assert c == cin
+    cout, K = W_b.shape
+    assert K == cin * kh * kw
+    if M is not None:
+        M = _c(M, np.uint8)
+        assert M.shape == (cout, K)
+    if scale is not None:
+        scale = _c(scale, np.float32)
+        assert scale.shape == (cout,)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+        assert bias.shape == (cout,)
+    return x_b, W_b, M, scale, bias, N, H, Wd, cout
+
+
+def conv2d_f8(x_b, W_b, M, *, cin, kh, kw, korder=K_CRS, scale=None, bias=None, stride=(1, 1), pad=(0, 0),
+              act=ACT_NONE) -> np.ndarray:
+    """Masked convolution on E4M3 bytes: fp64 products and sums, then act(scale[o] * sum + bias[o]), not rounded."""
+    x_b, W_b, M, scale, bias, N, H, Wd, cout = _f8_args(x_b, W_b, M, scale, bias, cin, kh, kw)
+    Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("empty output")
+    y = np.empty((N, Ho, Wo, cout), dtype=np.float64)
+    st = _load().ss_oracle_conv2d_f8(_ptr(x_b), N, H, Wd, cin, _ptr(W_b), _ptr(M), cout, kh, kw, korder, _ptr(scale),
+                                     _ptr(bias), stride[0], stride[1], pad[0], pad[1], act, _ptr(y))
+    if st:
+        raise ValueError(f"oracle conv2d_f8 failed (status {st})")
+    return y
+
+
+def conv2d_f8_points(x_b, W_b, M, flat_idx, *, cin, kh, kw, korder=K_CRS, scale=None, bias=None, stride=(1, 1),
+                     pad=(0, 0), act=ACT_NONE) -> np.ndarray:
+    x_b, W_b, M, scale, bias, N, H, Wd, cout = _f8_args(x_b, W_b, M, scale, bias, cin, kh, kw)
+    flat_idx = _c(flat_idx, np.int64)
+    Ho, Wo = _out_hw(H, Wd, kh, kw, stride, pad)
+    assert flat_idx.min() >= 0 and flat_idx.max() < N * Ho * Wo * cout
+    out = np.empty(flat_idx.shape, dtype=np.float64)
+    st = _load().ss_oracle_conv2d_f8_points(_ptr(x_b), N, H, Wd, cin, _ptr(W_b), _ptr(M), cout, kh, kw, korder,
+                                            _ptr(scale), _ptr(bias), stride[0], stride[1], pad[0], pad[1], act,
+                                            _ptr(flat_idx), flat_idx.size, _ptr(out))
+    if st:
+        raise ValueError(f"oracle conv2d_f8_points failed (status {st})")
     return out

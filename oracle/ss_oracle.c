@@ -37,6 +37,8 @@
  * conversions (all 65536 patterns x a spread of addends: ties, carries, subnormals, overflow).
  * The 8-bit integer functions are pinned against an int64 unfold + matmul in numpy, a float64 library convolution
  * (exact on these integers), the 16-bit functions above on the same small integers, and closed forms.
+ * The FP8 functions are pinned by a library's E4M3 conversion on all 256 bytes, closed-form values, and the binary16
+ * functions above on the same values (every E4M3 value is exact in binary16).
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -414,6 +416,88 @@ int ss_oracle_conv2d_q8_points(const int8_t *x, int64_t N, int64_t H, int64_t Wd
         int64_t ho = f % Ho; f /= Ho;
         int64_t acc = q8_sum(x, H, Wd, cin, W, M, kh, kw, korder, stride_h, stride_w, pad_h, pad_w, f, ho, wo, o);
         double z = (double)acc * (scale ? (double)scale[o] : 1.0);
+        if (bias) z += (double)bias[o];
+        out[i] = layer_tail(z, act);
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * 8-bit float precision point: operands are OCP FP8 E4M3 bytes (1 sign, 4 exponent bits with bias 7, 3 fraction
+ * bits; no infinities; S.1111.111 is NaN; exponent field 0 holds the subnormals m/8 * 2^-6).  Same definition as
+ * above with every byte widened exactly to fp64, fp64 products and sums, and the tail act(scale[o]*sum + bias[o]).
+ * --------------------------------------------------------------------------------------------- */
+double ss_oracle_e4m3_to_double(uint8_t b)
+{
+    int sign = b >> 7, expo = (b >> 3) & 0xf, frac = b & 7;
+    double v;
+    if (expo == 15 && frac == 7) return NAN;
+    if (expo == 0) v = ldexp((double)frac, -9);               /* frac/8 * 2^-6 */
+    else v = ldexp((double)(8 + frac), expo - 10);            /* (1 + frac/8) * 2^(expo-7) */
+    return sign ? -v : v;
+}
+
+static double f8_sum(const uint8_t *x, int64_t H, int64_t Wd, int64_t cin, const uint8_t *W, const uint8_t *M,
+                     int64_t kh, int64_t kw, int korder, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                     int64_t pad_w, int64_t n, int64_t ho, int64_t wo, int64_t o)
+{
+    int64_t K = cin * kh * kw;
+    double acc = 0.0;
+    for (int64_t c = 0; c < cin; c++)
+        for (int64_t r = 0; r < kh; r++) {
+            int64_t ih = ho * stride_h - pad_h + r;
+            if (ih < 0 || ih >= H) continue;                  /* zero padding */
+            for (int64_t t = 0; t < kw; t++) {
+                int64_t iw = wo * stride_w - pad_w + t;
+                if (iw < 0 || iw >= Wd) continue;             /* zero padding */
+                int64_t k = kflat(korder, c, r, t, cin, kh, kw);
+                if (M != NULL && !M[o * K + k]) continue;     /* M (.) W */
+                acc += ss_oracle_e4m3_to_double(W[o * K + k]) *
+                       ss_oracle_e4m3_to_double(x[((n * H + ih) * Wd + iw) * cin + c]);
+            }
+        }
+    return acc;
+}
+
+int ss_oracle_conv2d_f8(const uint8_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin, const uint8_t *W,
+                        const uint8_t *M, int64_t cout, int64_t kh, int64_t kw, int korder, const float *scale,
+                        const float *bias, int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                        int act, double *y)
+{
+    int64_t Ho = (H + 2 * pad_h - kh) / stride_h + 1;
+    int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
+    if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t ho = 0; ho < Ho; ho++)
+            for (int64_t wo = 0; wo < Wo; wo++)
+                for (int64_t o = 0; o < cout; o++) {
+                    double z = f8_sum(x, H, Wd, cin, W, M, kh, kw, korder, stride_h, stride_w, pad_h, pad_w,
+                                      n, ho, wo, o) * (scale ? (double)scale[o] : 1.0);
+                    if (bias) z += (double)bias[o];
+                    y[((n * Ho + ho) * Wo + wo) * cout + o] = layer_tail(z, act);
+                }
+    return 0;
+}
+
+int ss_oracle_conv2d_f8_points(const uint8_t *x, int64_t N, int64_t H, int64_t Wd, int64_t cin, const uint8_t *W,
+                               const uint8_t *M, int64_t cout, int64_t kh, int64_t kw, int korder,
+                               const float *scale, const float *bias, int64_t stride_h, int64_t stride_w,
+                               int64_t pad_h, int64_t pad_w, int act, const int64_t *flat_idx, int64_t npts,
+                               double *out)
+{
+    int64_t Ho = (H + 2 * pad_h - kh) / stride_h + 1;
+    int64_t Wo = (Wd + 2 * pad_w - kw) / stride_w + 1;
+    if (H + 2 * pad_h < kh || Wd + 2 * pad_w < kw || Ho <= 0 || Wo <= 0) return 3;
+    (void)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < npts; i++) {
+        int64_t f = flat_idx[i];
+        int64_t o = f % cout; f /= cout;
+        int64_t wo = f % Wo; f /= Wo;
+        int64_t ho = f % Ho; f /= Ho;
+        double z = f8_sum(x, H, Wd, cin, W, M, kh, kw, korder, stride_h, stride_w, pad_h, pad_w, f, ho, wo, o) *
+                   (scale ? (double)scale[o] : 1.0);
         if (bias) z += (double)bias[o];
         out[i] = layer_tail(z, act);
     }

@@ -19,7 +19,7 @@ from dataclasses import dataclass, field, replace
 
 import numpy as np
 
-F16, BF16, I8 = 0, 1, 2
+F16, BF16, I8, F8 = 0, 1, 2, 3
 K_CRS, K_RSC = 0, 1
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
@@ -70,7 +70,7 @@ class Layer:
 
     def algorithmic_bytes(self, sparse: bool = True) -> int:
         """x read once + y written once + weights (+ indices) + bias."""
-        if self.dtype == I8:     # int8 operands, 16-bit output, fp32 scale and bias per channel
+        if self.dtype in (I8, F8):     # 8-bit operands, 16-bit output, fp32 scale and bias per channel
             xb = self.N * self.H * self.W * self.cin
             wb = (self.cout * self.K // 2 + self.cout * self.K // 8) if sparse else self.cout * self.K
             return xb + 2 * self.P * self.cout + wb + 8 * self.cout
@@ -174,6 +174,46 @@ def make_inputs_q8(L: Layer) -> dict:
     else:
         raise ValueError(L.mask)
     return {"W": Wq, "M": M, "x": xq, "scale": (w_step * x_step).astype(np.float32), "bias": bias}
+
+
+def to_e4m3(a: np.ndarray) -> np.ndarray:
+    """float32 array -> OCP FP8 E4M3 bytes (uint8), round-to-nearest-even, saturating at +-448 (a storage cast of the
+    inputs, done by the tensor library)."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).clamp_(-448.0, 448.0)
+    return t.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def make_inputs_f8(L: Layer) -> dict:
+    """The FP8 (E4M3) variant of a layer: (W bytes [cout,K], M, x bytes NHWC, scale fp32, bias fp32).
+
+    Same draws as make_inputs; weights are divided per output channel by max|w| / 448 and activations by 4 / 448
+    (four standard deviations map to the format's largest value) before the cast; `scale` is the product of the two
+    divisors.  "top2" masks rank the magnitudes of the cast bytes (sign bit dropped: E4M3 is monotone in the rest)."""
+    rng = np.random.Generator(np.random.PCG64(L.seed))
+    w = rng.standard_normal((L.cout, L.cin, L.kh, L.kw), dtype=np.float32) * np.float32(np.sqrt(2.0 / L.K))
+    x = rng.standard_normal((L.N, L.H, L.W, L.cin), dtype=np.float32)
+    if L.relu_input:
+        np.maximum(x, 0, out=x)
+    bias = rng.standard_normal(L.cout, dtype=np.float32) * np.float32(0.1)
+    w_step = np.abs(w).reshape(L.cout, -1).max(axis=1) / np.float32(448.0)
+    w_step = np.where(w_step > 0, w_step, np.float32(1.0)).astype(np.float32)
+    Wb = flatten_weight(to_e4m3(w / w_step[:, None, None, None]), L.korder)
+    x_step = np.float32(4.0 / 448.0)
+    xb = to_e4m3(x / x_step)
+    if L.mask == "none":
+        M = None
+    elif L.mask == "top2":
+        mag = (Wb & 0x7F).astype(np.int32).reshape(L.cout, L.K // 4, 4)
+        order = np.argsort(-mag, axis=-1, kind="stable")
+        M = np.zeros((L.cout, L.K // 4, 4), dtype=np.uint8)
+        np.put_along_axis(M, order[..., :2], 1, axis=-1)
+        M = M.reshape(L.cout, L.K)
+    elif L.mask == "logits":
+        M = mask_from_logits(rng.standard_normal((L.cout, L.K // 4, 6), dtype=np.float32))
+    else:
+        raise ValueError(L.mask)
+    return {"W": Wb, "M": M, "x": xb, "scale": (w_step * x_step).astype(np.float32), "bias": bias}
 
 
 def make_weights(L: Layer, scale: float = 1.0) -> dict:
