@@ -87,20 +87,27 @@ class LayerRun:
 
 
 class Q8Run:
-    """The 8-bit integer variant of a layer (channels-last flattening): device operands drawn on the GPU for timing
-    (int8 weights ~ N(0, 40) clipped, activations ReLU(N(0, 32)) clipped, random 2:4 patterns, per-channel scale)."""
+    """The 8-bit variant of a layer (channels-last flattening), int8 or FP8 E4M3: device operands drawn on the GPU
+    for timing (weights ~ N(0, 40) and activations ReLU(N(0, 32)), clipped and cast; random 2:4 patterns; a
+    per-channel scale)."""
 
-    def __init__(self, L, torch, ss, wl):
+    def __init__(self, L, torch, ss, wl, dtype=None):
         self.L = L
+        dtype = ss.SS_I8 if dtype is None else dtype
         korder = wl.K_RSC if L.kh * L.kw > 1 else L.korder
-        self.desc = ss.make_desc(L.cout, L.cin, L.kh, L.kw, ss.SS_I8, korder)
+        self.desc = ss.make_desc(L.cout, L.cin, L.kh, L.kw, dtype, korder)
         g = torch.Generator(device="cuda").manual_seed(L.seed)
-        W = (torch.randn((L.cout, L.K), generator=g, device="cuda") * 40).clamp_(-127, 127).round_().to(torch.int8)
+
+        def cast(t):
+            if dtype == ss.SS_I8:
+                return t.clamp_(-127, 127).round_().to(torch.int8)
+            return t.clamp_(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8)
+        W = cast(torch.randn((L.cout, L.K), generator=g, device="cuda") * 40)
         pat = torch.tensor([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]],
                            dtype=torch.uint8, device="cuda")
         M = pat[torch.randint(0, 6, (L.cout, L.K // 4), generator=g, device="cuda")].reshape(L.cout, L.K).contiguous()
         x = torch.randn((L.N, L.H, L.W, L.cin), generator=g, device="cuda") * 32
-        x = (x.clamp_(min=0) if L.relu_input else x).clamp_(-127, 127).round_().to(torch.int8)
+        x = cast(x.clamp_(min=0) if L.relu_input else x)
         self.scale = torch.full((L.cout,), 1.0 / (40 * 32 * (L.K / 2) ** 0.5), device="cuda")
         self.bias = torch.randn(L.cout, generator=g, device="cuda") * 0.1
         self.packed = ss.ss_mask_compress(self.desc, W, M)
@@ -111,9 +118,10 @@ class Q8Run:
         self.keep = (W, M, x)
 
 
-def q8_point(torch, ss, wl, L, steps, warmup, reps=3):
-    """Sparse / dense-twin time of the 8-bit variant of a layer and its rate in dense-equivalent TOP/s."""
-    run = Q8Run(L, torch, ss, wl)
+def q8_point(torch, ss, wl, L, steps, warmup, reps=3, dtype=None):
+    """Sparse / dense-twin time of the 8-bit variant of a layer and its rate in dense-equivalent TOP/s (the published
+    dense peaks of int8 and fp8 are the same, 5.0 P/s, so one sparse peak serves both)."""
+    run = Q8Run(L, torch, ss, wl, dtype)
     ts = median_time(torch, run.sparse, steps, warmup, reps=reps)
     td = median_time(torch, run.densef, steps, warmup, reps=reps)
     tops = L.dense_equiv_flop / ts / 1e9
@@ -127,22 +135,26 @@ def print_q8_table(torch, ss, wl, steps, warmup):
     import dataclasses
     layers = [wl.CONFIG1, wl.with_batch(wl.CONFIG1, 500), wl.with_batch(wl.CONFIG1, 512), wl.CONFIG2]
     layers += [L for L in wl.resnet50_layers(64) if L.mask != "none" and L.cin % 16 == 0]
-    print(f"{'layer':34s} {'N':>4s} {'int8 us':>9s} {'twin us':>9s} {'x':>5s} {'TOP/s':>8s} {'16-bit us':>10s} {'int8 gain':>9s}")
-    tot8 = tot16 = totd = 0.0
+    print(f"{'layer':34s} {'N':>4s} {'int8 us':>9s} {'twin us':>9s} {'x':>5s} {'TOP/s':>8s} {'16-bit us':>10s} {'int8 gain':>9s}"
+          f" {'fp8 us':>8s} {'twin us':>8s} {'x':>5s}")
+    tot8 = tot16 = totd = totf = totfd = 0.0
     for i, L in enumerate(layers):
         r = q8_point(torch, ss, wl, L, steps, warmup)
+        rf = q8_point(torch, ss, wl, L, steps, warmup, dtype=ss.SS_F8)
         L16 = dataclasses.replace(L, korder=wl.K_RSC if L.kh * L.kw > 1 else L.korder)
         run16 = LayerRun(L16, torch, ss, wl, values=False)
         t16 = median_time(torch, run16.sparse, steps, warmup, reps=3) * 1e3
         del run16
         print(f"{L.name:34s} {L.N:4d} {r['sparse_us']:9.1f} {r['dense_twin_us']:9.1f} {r['speedup']:5.2f} {r['tops']:8.0f} "
-              f"{t16:10.1f} {t16 / r['sparse_us']:9.2f}", flush=True)
+              f"{t16:10.1f} {t16 / r['sparse_us']:9.2f} {rf['sparse_us']:8.1f} {rf['dense_twin_us']:8.1f} {rf['speedup']:5.2f}", flush=True)
         if i >= 4:      # the ResNet-50 layers
             tot8 += r["sparse_us"] * L.count
             totd += r["dense_twin_us"] * L.count
             tot16 += t16 * L.count
+            totf += rf["sparse_us"] * L.count
+            totfd += rf["dense_twin_us"] * L.count
     print(f"ResNet-50 masked layers, batch 64: int8 sparse {tot8 / 1e3:.3f} ms, int8 dense twin {totd / 1e3:.3f} ms, "
-          f"16-bit sparse {tot16 / 1e3:.3f} ms")
+          f"16-bit sparse {tot16 / 1e3:.3f} ms, fp8 sparse {totf / 1e3:.3f} ms, fp8 dense twin {totfd / 1e3:.3f} ms")
 
 
 def time_graph(torch, fn, steps: int, warmup: int) -> float:
@@ -409,6 +421,8 @@ def main():
     # the 8-bit integer precision point on the same shape (channels-last flattening), N = 32 and N = 500
     q8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50))
     q8_big = q8_point(torch, ss, wl, Leven, 20, 3)
+    f8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50), dtype=ss.SS_F8)
+    f8_big = q8_point(torch, ss, wl, Leven, 20, 3, dtype=ss.SS_F8)
     tc = time_launches(torch, lambda: ss.ss_mask_compress(run.desc, run.W, run.M, packed=run.packed), 20, 3)
     Wu, Uz = run.W.clone(), torch.zeros_like(run.W)     # a zero update: the packed weights stay what they are
     tu = time_launches(torch, lambda: ss.ss_mask_update_compress(run.desc, Wu, Uz, run.M, packed=run.packed), 20, 3)
@@ -432,6 +446,8 @@ def main():
                                      "frac_sparse_peak": Leven.dense_equiv_flop / te_s / 1e9 / SPARSE_PEAK_TFLOPS},
         "int8": {"workload": "same shape with int8 operands (channels-last flattening), fp16 output", "n32": q8_small,
                  "n500": q8_big, "peak_tops": SPARSE_INT8_PEAK_TOPS},
+        "fp8": {"workload": "same shape with FP8 E4M3 operands (channels-last flattening), fp16 output", "n32": f8_small,
+                "n500": f8_big, "peak_tflops": SPARSE_INT8_PEAK_TOPS},
         "compress_us": tc * 1e3, "update_compress_us": tu * 1e3, "eager_launch_us": eager_ms * 1e3,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": CFG1_TRAFFIC_BYTES,

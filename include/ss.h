@@ -23,11 +23,13 @@
  *   - 16-bit element types: SS_F16 (IEEE binary16) and SS_BF16 (bfloat16).  Activations, weights
  *     and outputs of one call share the type.  Products are accumulated in fp32, the bias is
  *     fp32, and the result is rounded once (round-to-nearest-even) when it is stored.
- *   - 8-bit integer operands (SS_I8): a further precision point beyond the 16-bit floats the paper uses.
- *     Weights and activations are signed bytes, products are accumulated exactly in int32, and the
- *     output is the 16-bit float act(scale[o]*sum + bias[o]); see ss_conv2d_q8_fwd.  The packing
- *     functions take SS_I8 descriptors (layout below); ss_mask_update_compress and the 16-bit
- *     convolution entry points reject them with SS_ERR_UNSUPPORTED.
+ *   - 8-bit operands (SS_I8, SS_F8): further precision points beyond the 16-bit floats the paper uses.
+ *     SS_I8: weights and activations are signed bytes, products are accumulated exactly in int32.
+ *     SS_F8: weights and activations are OCP FP8 E4M3 bytes, products (exact in fp32) are accumulated
+ *     in fp32.  Either way the output is the 16-bit float act(scale[o]*sum + bias[o]); see
+ *     ss_conv2d_q8_fwd.  The packing functions take such descriptors (layout below, the same for both:
+ *     bytes are copied, never interpreted); ss_mask_update_compress and the 16-bit convolution entry
+ *     points reject them with SS_ERR_UNSUPPORTED.
  *   - Activations and outputs are NHWC: x[N][H][Wd][cin], y[N][Ho][Wo][cout], with
  *     Ho = floor((H + 2*pad_h - kh)/stride_h) + 1 and likewise Wo.  Zero padding, no dilation,
  *     no groups (grouped convolutions are left dense by the method, Sec. 4 "Architectures").
@@ -60,14 +62,14 @@ enum {
     SS_ERR_HIP         = -5  /* a HIP runtime call failed (launch error, no device, ...) */
 };
 
-enum { SS_F16 = 0, SS_BF16 = 1, SS_I8 = 2 };
+enum { SS_F16 = 0, SS_BF16 = 1, SS_I8 = 2, SS_F8 = 3 /* OCP FP8 E4M3 (no infinities; S.1111.111 = NaN) */ };
 enum { SS_K_CRS = 0, SS_K_RSC = 1 };
 enum { SS_ACT_NONE = 0, SS_ACT_RELU = 1, SS_ACT_GELU = 2 };
 
 /* Describes one weight matrix W in R^{cout x (cin*kh*kw)} (Eq. 5).  Plain data, passed by pointer [host]. */
 typedef struct {
     int32_t cout, cin, kh, kw;
-    int32_t dtype;  /* SS_F16 | SS_BF16 | SS_I8 (weights and activations; see "8-bit integer operands") */
+    int32_t dtype;  /* SS_F16 | SS_BF16 | SS_I8 | SS_F8 (weights and activations; see "8-bit operands") */
     int32_t korder; /* SS_K_CRS | SS_K_RSC */
 } ss_weight_desc;
 
@@ -96,12 +98,12 @@ const char *ss_status_string(int status);
  * This is the operand layout of gfx950's V_SMFMAC_F32_32X32X32_{F16,BF16} (sparse A operand and
  * its index register), so the convolution loads it straight into registers.
  *
- * SS_I8: same header ([6] = 2) and tile sizes, with Ks = ceil(K/64) reduction steps of 64 indices:
+ * SS_I8 / SS_F8: same header ([6] = dtype) and tile sizes, with Ks = ceil(K/64) reduction steps of 64 indices:
  *   values               tile (mt, ks): 64 lanes x 16 bytes.  Lane l, slot s holds, for row 32*mt + l%32 and
  *                        block g = 16*ks + 8*(s/8) + 4*(l/32) + (s%8)/2, the (s%2)-th kept weight.
  *   metadata             Mt*Ks tiles of 64 uint32, after the values; lane l of tile (mt, ks) holds eight
  *                        nibbles, nibble j = i0 | (i1 << 2) for the block in slots 2j, 2j+1.
- * (the operand layout of V_SMFMAC_I32_32X32X64_I8).
+ * (the operand layout of V_SMFMAC_I32_32X32X64_I8 and V_SMFMAC_F32_32X32X64_FP8_FP8).
  */
 int ss_packed_bytes(const ss_weight_desc *desc, size_t *packed_bytes /*[host] out*/);
 
@@ -110,7 +112,7 @@ int ss_packed_bytes(const ss_weight_desc *desc, size_t *packed_bytes /*[host] ou
  * ss_conv2d_dense_fwd reads: a 256-byte header as above (magic 0x44325353) followed by
  * Mt*Ks*2 tiles of 64 lanes x 8 elements; tile (mt, ks, h) lane l slot s holds
  * (M (.) W)[32*mt + l%32][32*ks + 16*(l/32) + 8*h + s], zero where out of range.
- * SS_I8: tiles of 64 lanes x 16 bytes, Ks = ceil(K/64); tile (mt, ks, h) lane l slot s holds
+ * SS_I8 / SS_F8: tiles of 64 lanes x 16 bytes, Ks = ceil(K/64); tile (mt, ks, h) lane l slot s holds
  * (M (.) W)[32*mt + l%32][64*ks + 32*(l/32) + 16*h + s].
  */
 int ss_dense_bytes(const ss_weight_desc *desc, size_t *dense_bytes /*[host] out*/);
@@ -217,23 +219,25 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
                             void *y, void *workspace, size_t ws_bytes, void *stream);
 
 /*
- * The masked convolution on 8-bit integer operands: Eq. (6) with every product and the running sum
- * exact in int32, followed by the dequantising layer tail
+ * The masked convolution on 8-bit operands: Eq. (6) with every product and the running sum exact in
+ * int32 (SS_I8), or with exact products summed in fp32 (SS_F8), followed by the dequantising layer tail
  *     y[n,ho,wo,o] = act( scale[o] * sum_k (M (.) W)[o,k] * U(X)[k,p] + bias[o] ),
- * evaluated in fp32 (the int32 sum is converted with round-to-nearest-even) and rounded once to the
+ * evaluated in fp32 (an int32 sum is converted with round-to-nearest-even) and rounded once to the
  * output type.  The paper stops at 16-bit floats; this is the same method one precision step further,
- * on gfx950's V_SMFMAC_I32_32X32X64_I8, which consumes twice the reduction length per instruction.
- *   desc    dtype SS_I8; cin % 16 == 0; korder SS_K_RSC unless kh = kw = 1 (in the channel-slowest
+ * on gfx950's V_SMFMAC_I32_32X32X64_I8 / V_SMFMAC_F32_32X32X64_FP8_FP8, which consume twice the
+ * reduction length per instruction.
+ *   desc    dtype SS_I8 or SS_F8; cin % 16 == 0; korder SS_K_RSC unless kh = kw = 1 (in the channel-slowest
  *           flattening a 4-block spans kernel taps, i.e. bytes of different pixels, which the 16-byte
  *           staging of this path does not gather) -- otherwise SS_ERR_UNSUPPORTED
- *   x       [N][H][Wd][cin] int8, 16-byte aligned                                   (read only)
+ *   x       [N][H][Wd][cin] bytes of desc->dtype, 16-byte aligned                   (read only)
  *   packed  written by ss_mask_compress for this descriptor                         (read only)
  *   scale   [cout] fp32 or NULL (= 1): weight step * activation step of the quantiser (read only)
  *   bias    [cout] fp32 or NULL (= 0)                                               (read only)
  *   act     SS_ACT_NONE | SS_ACT_RELU | SS_ACT_GELU
  *   out_dtype  SS_F16 (the only one built; anything else SS_ERR_UNSUPPORTED)
  *   y       [N][Ho][Wo][cout] 16-bit, 16-byte aligned                               (written)
- *   |sum| must stay below 2^31: K * 128 * 128 < 2^31, i.e. K <= 131071 (else SS_ERR_UNSUPPORTED).
+ *   SS_I8: |sum| must stay below 2^31: K * 128 * 128 < 2^31, i.e. K <= 131071 (else SS_ERR_UNSUPPORTED).
+ *   SS_F8: a NaN byte propagates; sums beyond fp32 range cannot occur (K * 448^2 < 2^128).
  * Everything else (workspace, stream, errors) as for ss_conv2d_fwd.
  */
 int ss_conv2d_q8_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
@@ -241,7 +245,8 @@ int ss_conv2d_q8_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32
                      int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
                      int32_t out_dtype, void *y, void *workspace, size_t ws_bytes, void *stream);
 
-/* The dense twin of ss_conv2d_q8_fwd (V_MFMA_I32_32X32X32_I8 on the operand built by ss_dense_pack). */
+/* The dense twin of ss_conv2d_q8_fwd (V_MFMA_I32_32X32X32_I8, or V_MFMA_SCALE_F32_32X32X64_F8F6F4 with unit
+ * scales, on the operand built by ss_dense_pack). */
 int ss_conv2d_q8_dense_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
                            const void *dense, const float *scale, const float *bias,
                            int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,

@@ -16,7 +16,7 @@ LIB_PATH = _HERE / "libss.so"
 
 SS_OK = 0
 SS_ERR_INVALID_ARG, SS_ERR_BAD_MASK, SS_ERR_UNSUPPORTED, SS_ERR_WORKSPACE, SS_ERR_HIP = -1, -2, -3, -4, -5
-SS_F16, SS_BF16, SS_I8 = 0, 1, 2
+SS_F16, SS_BF16, SS_I8, SS_F8 = 0, 1, 2, 3
 SS_K_CRS, SS_K_RSC = 0, 1
 SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 
@@ -102,16 +102,16 @@ def _dev_ptr(t, name, dtypes=None, allow_none=False):
 
 
 _T16 = (torch.float16, torch.bfloat16, torch.int16, torch.uint16)
-_T8 = (torch.int8, torch.uint8)
+_T8 = (torch.int8, torch.uint8, torch.float8_e4m3fn)
 
 
 def _wtypes(desc):
     """Tensor dtypes accepted for weights of a descriptor."""
-    return _T8 if desc.dtype == SS_I8 else _T16
+    return _T8 if desc.dtype in (SS_I8, SS_F8) else _T16
 
 
 def torch_dtype(dtype: int):
-    return {SS_F16: torch.float16, SS_BF16: torch.bfloat16, SS_I8: torch.int8}[dtype]
+    return {SS_F16: torch.float16, SS_BF16: torch.bfloat16, SS_I8: torch.int8, SS_F8: torch.uint8}[dtype]
 
 
 def ss_packed_bytes(desc: ss_weight_desc) -> int:
@@ -312,7 +312,8 @@ def _q8_args(what, desc, x, wbuf, scale, bias, stride, pad, act, y, workspace):
     if need > 0 and workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         ws_bytes = need
-    args = (ctypes.byref(desc), _dev_ptr(x, "x", (torch.int8,)), N, H, W, _dev_ptr(wbuf, "weights"),
+    xtypes = (torch.int8,) if desc.dtype == SS_I8 else (torch.uint8, torch.float8_e4m3fn)
+    args = (ctypes.byref(desc), _dev_ptr(x, "x", xtypes), N, H, W, _dev_ptr(wbuf, "weights"),
             _dev_ptr(scale, "scale", (torch.float32,), allow_none=True),
             _dev_ptr(bias, "bias", (torch.float32,), allow_none=True), stride[0], stride[1], pad[0], pad[1], act,
             SS_F16, _dev_ptr(y, "y"), _dev_ptr(workspace, "workspace", allow_none=True), ws_bytes)
@@ -336,7 +337,8 @@ def prepare_conv2d_q8(desc, x, wbuf, scale=None, bias=None, stride=(1, 1), pad=(
 
 def ss_conv2d_q8_fwd(desc, x, packed, scale=None, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
                      workspace=None, stream=None) -> torch.Tensor:
-    """2:4-sparse convolution on int8 operands: x NHWC int8 -> y NHWC float16 = act(scale * sum + bias)."""
+    """2:4-sparse convolution on 8-bit operands (int8, or FP8 E4M3 bytes): x NHWC -> y NHWC float16 =
+    act(scale * sum + bias)."""
     args, y, _ws = _q8_args("ss_conv2d_q8_fwd", desc, x, packed, scale, bias, stride, pad, act, y, workspace)
     st = _lib.ss_conv2d_q8_fwd(*args, _stream_ptr(stream))
     if st != SS_OK:

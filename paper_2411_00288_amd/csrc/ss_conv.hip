@@ -34,10 +34,10 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 
-// Accumulators of one 32x32 tile: fp32 for the 16-bit floats, int32 (exact) for 8-bit integers.
+// Accumulators of one 32x32 tile: fp32 for the floats (16-bit and FP8), int32 (exact) for 8-bit integers.
 template <int DT> using Acc = typename std::conditional<DT == SS_I8, i32x16, f32x16>::type;
-// Type of the 16-bit output (and of a residual): the operands' own, or binary16 for integer operands.
-template <int DT> constexpr int out_type() { return DT == SS_I8 ? SS_F16 : DT; }
+// Type of the 16-bit output (and of a residual): the operands' own, or binary16 for 8-bit operands.
+template <int DT> constexpr int out_type() { return is_byte_type(DT) ? SS_F16 : DT; }
 
 struct B32 {   // one lane's B fragment for a reduction step: 32 bytes (16 x 16-bit, or 32 x int8)
     u32x4 lo, hi;
@@ -75,7 +75,7 @@ __device__ __forceinline__ int fast_div(int n, unsigned mul, unsigned sh)
 constexpr unsigned kOutOfRange = 0x80000000u;   // >= any buffer size used here: the load returns 0
 constexpr int kRsrcFlags = 0x00020000;          // raw buffer, 32-bit data format (gfx9 family)
 
-// The 8-bit integer instruction (32x32x64) pairs slot s of A lane l (16 kept bytes, index field s of a full index
+// The 8-bit instructions (32x32x64, integer and FP8 alike) pair slot s of A lane l (16 kept bytes, index field s of a full index
 // word) with bytes 16*(l/32) + 4*((s%8)/2) + idx of the B lane of the same column in lane group s/8; B lane
 // l holds the 32 reduction indices 32*(l/32) + [0,32) of pixel l%32.  Accumulators are laid out as above.
 template <int DT>
@@ -83,12 +83,23 @@ __device__ __forceinline__ Acc<DT> mma_sparse(u32x4 a, const B32 &b, Acc<DT> c, 
 {
     if constexpr (DT == SS_I8)
         return __builtin_amdgcn_smfmac_i32_32x32x64_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x8, b), c, (int)idx, 0, 0);
+    else if constexpr (DT == SS_F8)
+        return __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x8, b), c, (int)idx, 0, 0);
     else if constexpr (DT == SS_F16)
         return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x16, b), c,
                                                          (int)idx, 0, 0);
     else
         return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x16, b), c,
                                                           (int)idx, 0, 0);
+}
+
+// Dense FP8: one 32x32x64 instruction of the scaled-format family with both formats E4M3 and both block scales
+// 2^0 (exponent byte 127); A and B slots s of lane l are k = 32*(l/32) + s.
+__device__ __forceinline__ f32x16 mma_dense_f8(u32x4 a0, u32x4 a1, const B32 &b, f32x16 c)
+{
+    struct A32 { u32x4 lo, hi; } a = {a0, a1};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(__builtin_bit_cast(i32x8, a), __builtin_bit_cast(i32x8, b), c, 0, 0, 0,
+                                                           0x7F7F7F7F, 0, 0x7F7F7F7F);
 }
 
 template <int DT>
@@ -219,12 +230,12 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // wave's matrix instructions.
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC>
 __global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
-__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8))))
+__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : ((DT == SS_F8 && !SPARSE) ? 2 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8)))))   // (the dense FP8 instruction wants its 32-byte A operand in 8 consecutive registers: more pressure)
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
     static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
-    constexpr bool Q8 = DT == SS_I8;                      // 8-bit integer operands: staged as byte pairs, int32 sums
+    constexpr bool Q8 = is_byte_type(DT);                 // 8-bit operands: staged as byte pairs, full index words, scaled tail
     constexpr int ODT = out_type<DT>();
     static_assert(!Q8 || is_vec(MODE) || MODE == MODE_PW || MODE == MODE_PW2, "byte pairs travel in 16-byte runs only");
     constexpr int NMATH = WAVES_M * WAVES_N * 64;         // threads that multiply
@@ -605,6 +616,8 @@ void conv_kernel(ConvParams p)
                     for (int tn = 0; tn < TN; tn++) {
                         if constexpr (SPARSE) {
                             acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s % BD][tn], acc[tm][tn], as.idx[tm] >> idx_shift);
+                        } else if constexpr (DT == SS_F8) {
+                            acc[tm][tn] = mma_dense_f8(as.v[0][tm], as.v[1][tm], b[s % BD][tn], acc[tm][tn]);
                         } else {
                             acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[s % BD][tn].lo, acc[tm][tn]);
                             acc[tm][tn] = mma_dense<DT>(as.v[1][tm], b[s % BD][tn].hi, acc[tm][tn]);
@@ -613,7 +626,7 @@ void conv_kernel(ConvParams p)
                 // Scheduling: left alone, the compiler sinks every load to just before its first use and the
                 // prefetch distance collapses to zero.  Pin this step's instructions to the step (barriers at both
                 // ends) and interleave the loads for later steps between its matrix instructions.
-                constexpr int NMMA = TM * TN * (SPARSE ? 1 : 2);
+                constexpr int NMMA = TM * TN * ((SPARSE || DT == SS_F8) ? 1 : 2);
                 constexpr int DSR = (2 * TN + NMMA - 1) / NMMA;
                 constexpr int VMR = (TM * 2 + NMMA - 1) / NMMA;
 #pragma unroll
@@ -775,9 +788,9 @@ template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MOD
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr size_t scale_bytes = DT == SS_I8 ? (size_t)BM * 4 : 0;      // the per-channel scales sit behind the bias values
+    constexpr size_t scale_bytes = is_byte_type(DT) ? (size_t)BM * 4 : 0;      // the per-channel scales sit behind the bias values
     constexpr size_t smem_plain = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(false) + scale_bytes;
-    constexpr size_t smem_res = DT == SS_I8 ? smem_plain : smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
+    constexpr size_t smem_res = is_byte_type(DT) ? smem_plain : smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
     static_assert(smem_plain <= 160 * 1024 && smem_res <= 160 * 1024, "LDS tile too large");
     const size_t smem = p0.residual ? smem_res : smem_plain;
     ConvParams p = p0;
@@ -819,11 +832,18 @@ static inline long long n_blocks(const ConvParams &p, int bm, int bn)
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int launch_tile(int id, const ConvParams &p, hipStream_t s)
 {
+    if constexpr (MODE != MODE_VEC8) {       // (the long-chunk staging is only ever paired with the deep tiles)
+        switch (id) {
+            case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, false>(p, s);
+            case 1: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, true>(p, s);
+            case 2: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, false>(p, s);
+            default: break;
+        }
+    }
+    if constexpr (MODE != MODE_VEC8 || !is_byte_type(DT)) {
+        if (id == 3) return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true>(p, s);
+    }
     switch (id) {
-        case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, false>(p, s);
-        case 1: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, true>(p, s);
-        case 2: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, false>(p, s);
-        case 3: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true>(p, s);
         case 4: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, true>(p, s);
         case 5: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, true>(p, s);
         default: break;
@@ -873,7 +893,7 @@ static int pick_vec(const ConvParams &p, hipStream_t s)
 {
     if (p.K >= 512) {
         const int id = getenv("SS_TILE") ? atoi(getenv("SS_TILE")) : choose_tile(p, false, true);
-        if (id == 4 || id == 5 || (id == 3 && DT != SS_I8)) return pick_tile<DT, SPARSE, MODE_VEC8, 1, 1>(p, s);
+        if (id == 4 || id == 5 || (id == 3 && !is_byte_type(DT))) return pick_tile<DT, SPARSE, MODE_VEC8, 1, 1>(p, s);
     }
     return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
 }
@@ -882,7 +902,7 @@ template <int DT, bool SPARSE>
 static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_t s)
 {
     const int taps = desc->kh * desc->kw;
-    if constexpr (DT == SS_I8) {    // validated by the entry point: byte pairs are contiguous in every 16-byte run
+    if constexpr (is_byte_type(DT)) {    // validated by the entry point: byte pairs are contiguous in every 16-byte run
         if (taps == 1) return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
         return pick_vec<DT, SPARSE>(p, s);
     } else {
@@ -910,11 +930,11 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     (void)ws_bytes;
     int st = check_desc(desc, SPARSE);
     if (st != SS_OK) return st;
-    if ((desc->dtype == SS_I8) != q8) return q8 ? SS_ERR_INVALID_ARG : SS_ERR_UNSUPPORTED;
+    if (is_byte_type(desc->dtype) != q8) return q8 ? SS_ERR_INVALID_ARG : SS_ERR_UNSUPPORTED;
     const int esize = q8 ? 1 : 2;      // bytes per activation / weight element
     if (q8) {
         if (desc->cin % 16 != 0 || (desc->korder != SS_K_RSC && desc->kh * desc->kw != 1)) return SS_ERR_UNSUPPORTED;
-        if ((long long)desc->cin * desc->kh * desc->kw > 131071) return SS_ERR_UNSUPPORTED;      // int32 sums
+        if (desc->dtype == SS_I8 && (long long)desc->cin * desc->kh * desc->kw > 131071) return SS_ERR_UNSUPPORTED;      // int32 sums
         if (scale && !aligned(scale, 4)) return SS_ERR_INVALID_ARG;
     }
     if (!x || !wbuf || !y) return SS_ERR_INVALID_ARG;
@@ -957,7 +977,7 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.a_bytes = (unsigned)((size_t)t.Mt * t.Ks * (SPARSE ? 1024 : 2048));
     p.meta_bytes = SPARSE ? (unsigned)((size_t)t.Mt * t.Kp * 256) : 4u;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (q8) return pick_mode<SS_I8, SPARSE>(desc, p, s);
+    if (q8) return desc->dtype == SS_I8 ? pick_mode<SS_I8, SPARSE>(desc, p, s) : pick_mode<SS_F8, SPARSE>(desc, p, s);
     return desc->dtype == SS_F16 ? pick_mode<SS_F16, SPARSE>(desc, p, s) : pick_mode<SS_BF16, SPARSE>(desc, p, s);
 }
 

@@ -26,7 +26,7 @@ inline TileDims tile_dims(const ss_weight_desc *d)
     t.K = d->cin * d->kh * d->kw;
     t.G = t.K / 4;
     t.Mt = (d->cout + 31) / 32;
-    if (d->dtype == SS_I8) {          // reduction steps of 64 bytes, one index word per step
+    if (d->dtype == SS_I8 || d->dtype == SS_F8) {          // reduction steps of 64 bytes, one index word per step
         t.Ks = (t.K + 63) / 64;
         t.Kp = t.Ks;
     } else {
@@ -41,7 +41,7 @@ inline int check_desc(const ss_weight_desc *d, bool need_groups)
 {
     if (!d) return SS_ERR_INVALID_ARG;
     if (d->cout <= 0 || d->cin <= 0 || d->kh <= 0 || d->kw <= 0) return SS_ERR_INVALID_ARG;
-    if (d->dtype != SS_F16 && d->dtype != SS_BF16 && d->dtype != SS_I8) return SS_ERR_INVALID_ARG;
+    if (d->dtype != SS_F16 && d->dtype != SS_BF16 && d->dtype != SS_I8 && d->dtype != SS_F8) return SS_ERR_INVALID_ARG;
     if (d->korder != SS_K_CRS && d->korder != SS_K_RSC) return SS_ERR_INVALID_ARG;
     int64_t K = (int64_t)d->cin * d->kh * d->kw;
     if (K > (1 << 24) || (int64_t)d->cout * ((K + 63) / 64 * 64) >= (1ll << 31)) return SS_ERR_UNSUPPORTED;
@@ -57,6 +57,8 @@ inline size_t dense_size(const TileDims &t)
 {
     return (size_t)kHeaderBytes + (size_t)t.Mt * t.Ks * 2048;
 }
+
+constexpr bool is_byte_type(int dtype) { return dtype == SS_I8 || dtype == SS_F8; }
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

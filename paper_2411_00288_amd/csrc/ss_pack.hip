@@ -166,9 +166,9 @@ __global__ __launch_bounds__(256) void dense_pack_kernel(const uint16_t *__restr
 }
 
 // ---------------------------------------------------------------------------------------------
-// 8-bit integer operands.  One thread produces one lane of one value tile: 16 packed bytes and the 32 index
+// 8-bit operands (integer or FP8: bytes are copied, never interpreted).  One thread produces one lane of one value tile: 16 packed bytes and the 32 index
 // bits that go with them.  Lane l of tile (mt, ks) owns row 32*mt + l%32 and, in slots 2j, 2j+1 (j = 0..7),
-// block 16*ks + 8*(j/4) + 4*(l/32) + j%4: gfx950's 32x32x64 integer sparse MFMA pairs slot s of lane l with the
+// block 16*ks + 8*(j/4) + 4*(l/32) + j%4: gfx950's 32x32x64 8-bit sparse MFMAs pair slot s of lane l with the
 // bytes 16*(l/32) + 4*((s%8)/2) + [0,4) of the B lane of the same column in lane group s/8, and B lane groups
 // hold the reduction indices 64*ks + 32*group + [0,32).
 // ---------------------------------------------------------------------------------------------
@@ -307,7 +307,7 @@ static int compress_entry(const ss_weight_desc *desc, void *W, const void *U, co
     int st = check_desc(desc, true);
     if (st != SS_OK) return st;
     if (!W || !M || !packed) return SS_ERR_INVALID_ARG;
-    const bool i8 = desc->dtype == SS_I8;
+    const bool i8 = is_byte_type(desc->dtype);
     if (i8 && U) return SS_ERR_UNSUPPORTED;       // the update is defined on the 16-bit floats only
     if (!aligned(W, i8 ? 4 : 8) || !aligned(M, 4) || !aligned(packed, 16) || (U && !aligned(U, 8))) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
@@ -359,7 +359,7 @@ extern "C" int ss_mask_decompress(const ss_weight_desc *desc, const void *packed
     int st = check_desc(desc, true);
     if (st != SS_OK) return st;
     if (!packed || !W_masked_out) return SS_ERR_INVALID_ARG;
-    const bool i8 = desc->dtype == SS_I8;
+    const bool i8 = is_byte_type(desc->dtype);
     if (!aligned(packed, 16) || !aligned(W_masked_out, i8 ? 4 : 8)) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
     int total = desc->cout * t.G;
@@ -378,14 +378,14 @@ extern "C" int ss_dense_pack(const ss_weight_desc *desc, const void *W, const ui
     int st = check_desc(desc, false);
     if (st != SS_OK) return st;
     if (!W || !dense) return SS_ERR_INVALID_ARG;
-    if (!aligned(W, desc->dtype == SS_I8 ? 1 : 2) || !aligned(dense, 16)) return SS_ERR_INVALID_ARG;
+    if (!aligned(W, is_byte_type(desc->dtype) ? 1 : 2) || !aligned(dense, 16)) return SS_ERR_INVALID_ARG;
     TileDims t = tile_dims(desc);
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *p = static_cast<uint8_t *>(dense);
     write_header_kernel<<<1, 64, 0, s>>>(reinterpret_cast<uint32_t *>(p), kMagicDense, desc->cout, desc->cin,
                                          desc->kh, desc->kw, desc->dtype, desc->korder, t.Mt, t.Ks);
     int total = t.Mt * t.Ks * 2 * 64;
-    if (desc->dtype == SS_I8)
+    if (is_byte_type(desc->dtype))
         dense_pack8_kernel<<<(total + 255) / 256, 256, 0, s>>>(static_cast<const uint8_t *>(W), M, p, desc->cout, t.K,
                                                                t.Mt, t.Ks);
     else
