@@ -15,6 +15,10 @@
 //   of 4 consecutive output channels of one pixel.
 //   The dense twin issues two 32x32x16 dense MFMAs on the same B registers instead.
 //
+// 8-bit operands (int8, FP8 E4M3) run through the same kernel: activations are staged as 2-byte units (pairs of
+// channels), one 32x32x64 instruction then consumes the same 32 B of B and 16 B of A per lane as the 16-bit one
+// and does twice the multiply-adds; sums are int32 (exact) or fp32, and the tail multiplies by a per-channel scale.
+//
 // All global reads of activations and weights are raw buffer loads: a lane whose element lies in
 // the zero padding, past the last pixel or past the reduction length presents an offset beyond the
 // buffer's size and the hardware returns 0 -- no branches, no selects.
@@ -48,7 +52,7 @@ struct ConvParams {
     const uint8_t *a_vals;    // first value tile (after the header)
     const uint32_t *a_meta;   // first metadata tile (sparse only)
     const float *bias;
-    const float *scale;       // integer operands: per-output-channel factor of the int32 sum, or nullptr (= 1)
+    const float *scale;       // 8-bit operands: per-output-channel factor of the sum, or nullptr (= 1)
     const uint16_t *residual; // [P][Cout] like y, or nullptr
     uint16_t *y;
     int N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, Ho, Wo, P, K, Ks, Kp, Mt, act, korder;
@@ -287,7 +291,7 @@ void conv_kernel(ConvParams p)
                                               (with_res ? smem_body<BM, BN, MODE, KH, KW, DEEP>(true) : smem_body<BM, BN, MODE, KH, KW, DEEP>(false)));
     // (Loaded after the first activation / weight loads are on their way: issued first, its latency would
     // sit in front of everything else.)
-    float *scale_s = bias_s + BM;                     // (integer operands only)
+    float *scale_s = bias_s + BM;                     // (8-bit operands only)
     float bias_r[(BM + NMATH - 1) / NMATH], scale_r[Q8 ? (BM + NMATH - 1) / NMATH : 1];
     auto load_bias = [&]() {
 #pragma unroll
@@ -918,8 +922,8 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
     }
 }
 
-// q8: the call came through an 8-bit integer entry point (then `scale` may be given and the descriptor must say
-// SS_I8); the 16-bit entry points reject SS_I8 descriptors.
+// q8: the call came through an 8-bit entry point (then `scale` may be given and the descriptor must say SS_I8 or
+// SS_F8); the 16-bit entry points reject such descriptors.
 template <bool SPARSE>
 static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd, const void *wbuf,
                       const float *bias, const void *residual, int32_t sh, int32_t sw, int32_t ph, int32_t pw,
