@@ -226,9 +226,9 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
  * output type.  The paper stops at 16-bit floats; this is the same method one precision step further,
  * on gfx950's V_SMFMAC_I32_32X32X64_I8 / V_SMFMAC_F32_32X32X64_FP8_FP8, which consume twice the
  * reduction length per instruction.
- *   desc    dtype SS_I8 or SS_F8; cin % 16 == 0; korder SS_K_RSC unless kh = kw = 1 (in the channel-slowest
- *           flattening a 4-block spans kernel taps, i.e. bytes of different pixels, which the 16-byte
- *           staging of this path does not gather) -- otherwise SS_ERR_UNSUPPORTED
+ *   desc    dtype SS_I8 or SS_F8; cin % 16 == 0; with korder SS_K_CRS and a kernel larger than 1x1 (a
+ *           4-block then spans kernel taps, i.e. bytes of different pixels, which are transposed in
+ *           registers) only 3x3 and 2x2 kernels with cin % 64 == 0 -- otherwise SS_ERR_UNSUPPORTED
  *   x       [N][H][Wd][cin] bytes of desc->dtype, 16-byte aligned                   (read only)
  *   packed  written by ss_mask_compress for this descriptor                         (read only)
  *   scale   [cout] fp32 or NULL (= 1): weight step * activation step of the quantiser (read only)

@@ -101,9 +101,9 @@ __device__ __forceinline__ Acc<DT> mma_sparse(u32x4 a, const B32 &b, Acc<DT> c, 
 // 2^0 (exponent byte 127); A and B slots s of lane l are k = 32*(l/32) + s.
 __device__ __forceinline__ f32x16 mma_dense_f8(u32x4 a0, u32x4 a1, const B32 &b, f32x16 c)
 {
-    struct A32 { u32x4 lo, hi; } a = {a0, a1};
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(__builtin_bit_cast(i32x8, a), __builtin_bit_cast(i32x8, b), c, 0, 0, 0,
-                                                           0x7F7F7F7F, 0, 0x7F7F7F7F);
+    const i32x8 a = __builtin_shufflevector(__builtin_bit_cast(i32x4, a0), __builtin_bit_cast(i32x4, a1), 0, 1, 2, 3, 4, 5, 6, 7);
+    const i32x8 bb = __builtin_shufflevector(__builtin_bit_cast(i32x4, b.lo), __builtin_bit_cast(i32x4, b.hi), 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bb, c, 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
 }
 
 template <int DT>
@@ -166,7 +166,8 @@ __device__ __forceinline__ float normal_cdf(float v)
 //               different pixels.  A thread loads, for one output pixel and 8 channels, the
 //               KH*KW taps as 16-byte channel vectors and transposes them in registers to
 //               channel-major order before the LDS write, so the MFMA side still reads 16-byte
-//               vectors.  A chunk is 32 channels = KH*KW reduction steps.
+//               vectors.  A chunk is 32 channels = KH*KW reduction steps.  (8-bit operands: 16 channels per
+//               vector, a byte transpose, chunks of 64 channels.)
 enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2, MODE_PW = 3, MODE_PW2 = 4, MODE_VEC8 = 5 };
 constexpr bool is_vec(int mode) { return mode == MODE_VEC || mode == MODE_VEC8; }
 
@@ -241,7 +242,7 @@ void conv_kernel(ConvParams p)
     static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
     constexpr bool Q8 = is_byte_type(DT);                 // 8-bit operands: staged as byte pairs, full index words, scaled tail
     constexpr int ODT = out_type<DT>();
-    static_assert(!Q8 || is_vec(MODE) || MODE == MODE_PW || MODE == MODE_PW2, "byte pairs travel in 16-byte runs only");
+    static_assert(!Q8 || MODE != MODE_GATHER, "8-bit operands travel in 16-byte runs only");
     constexpr int NMATH = WAVES_M * WAVES_N * 64;         // threads that multiply
     constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
@@ -461,6 +462,27 @@ void conv_kernel(ConvParams p)
                 for (int v = 0; v < TAPS; v++) {
                     if (v < j * TAPS / n || v >= (j + 1) * TAPS / n) continue;
                     uint32_t o[4];
+                    if constexpr (Q8) {
+                        // bytes: [tap][16 channels] -> [channel][tap]; output byte h = c*TAPS + tap, four per dword, each
+                        // from its own tap's vector: two byte pairs are picked first, then joined
+#pragma unroll
+                        for (int q = 0; q < 4; q++) {
+                            const int d = 4 * v + q;
+                            uint32_t src[4], pick[4];
+#pragma unroll
+                            for (int e = 0; e < 4; e++) {
+                                const int h = 4 * d + e, c = h / TAPS, t = h % TAPS;
+                                src[e] = stage_t[i][t][c >> 2];
+                                pick[e] = (uint32_t)(c & 3);
+                            }
+                            const uint32_t p01 = __builtin_amdgcn_perm(src[1], src[0], pick[0] | ((4u + pick[1]) << 8));
+                            const uint32_t p23 = __builtin_amdgcn_perm(src[3], src[2], pick[2] | ((4u + pick[3]) << 8));
+                            o[q] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+                        }
+                        u32x4 w = {o[0], o[1], o[2], o[3]};
+                        dst[v] = w;
+                        continue;
+                    }
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
                         const int d = 4 * v + q;
@@ -908,7 +930,9 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
     const int taps = desc->kh * desc->kw;
     if constexpr (is_byte_type(DT)) {    // validated by the entry point: byte pairs are contiguous in every 16-byte run
         if (taps == 1) return p.Ks <= 2 ? pick_tile<DT, SPARSE, MODE_PW2, 1, 1>(p, s) : pick_tile<DT, SPARSE, MODE_PW, 1, 1>(p, s);
-        return pick_vec<DT, SPARSE>(p, s);
+        if (desc->korder == SS_K_RSC) return pick_vec<DT, SPARSE>(p, s);
+        if (desc->kh == 3) return pick_tile<DT, SPARSE, MODE_TAPS, 3, 3>(p, s);
+        return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);
     } else {
     // channels contiguous inside every aligned run of 8 reduction indices?
     if (desc->cin % 8 == 0 && taps == 1)
@@ -937,7 +961,11 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     if (is_byte_type(desc->dtype) != q8) return q8 ? SS_ERR_INVALID_ARG : SS_ERR_UNSUPPORTED;
     const int esize = q8 ? 1 : 2;      // bytes per activation / weight element
     if (q8) {
-        if (desc->cin % 16 != 0 || (desc->korder != SS_K_RSC && desc->kh * desc->kw != 1)) return SS_ERR_UNSUPPORTED;
+        if (desc->cin % 16 != 0) return SS_ERR_UNSUPPORTED;
+        if (desc->korder == SS_K_CRS && desc->kh * desc->kw != 1) {     // taps inside a block: the byte transpose
+            const bool square = (desc->kh == 3 && desc->kw == 3) || (desc->kh == 2 && desc->kw == 2);
+            if (!square || desc->cin % 64 != 0) return SS_ERR_UNSUPPORTED;
+        }
         if (desc->dtype == SS_I8 && (long long)desc->cin * desc->kh * desc->kw > 131071) return SS_ERR_UNSUPPORTED;      // int32 sums
         if (scale && !aligned(scale, 4)) return SS_ERR_INVALID_ARG;
     }

@@ -72,6 +72,8 @@ def test_packed_bytes_match_oracle_bit_for_bit(ss, shape):
 
 SHAPES = [
     _L(3, 14, 14, 64, 300, 3, p=1),
+    _L(2, 13, 11, 128, 200, 3, p=1, korder=wl.K_CRS, seed=6),   # the paper's flattening: byte transpose of the taps, 2 chunks of 64 channels
+    _L(2, 12, 12, 64, 136, 2, s=2, korder=wl.K_CRS, seed=7),    # 2x2 stride 2 in the paper's flattening
     _L(2, 9, 10, 128, 200, 3, p=1, seed=4),         # long-reduction staging
     _L(2, 15, 13, 96, 136, 3, s=2, p=1),
     _L(3, 9, 11, 160, 264, 1, korder=wl.K_CRS),
@@ -104,7 +106,7 @@ def test_convolution_matches_oracle(ss, L):
 
 
 @pytest.mark.parametrize("tile", TILE_IDS)
-@pytest.mark.parametrize("L", SHAPES[:6], ids=lambda L: L.name)
+@pytest.mark.parametrize("L", SHAPES[:8], ids=lambda L: L.name)
 def test_every_tile_shape_matches_oracle(ss, force_tile, L, tile):
     d = wl.make_inputs_f8(L)
     ref = _ref(L, d)

@@ -117,6 +117,8 @@ def test_compress_reports_first_invalid_block_and_rejects_updates(ss):
 
 SHAPES = [
     _L(3, 14, 14, 64, 300, 3, p=1),                 # 3x3, K = 576 bytes = 9 steps (ragged last chunk of 2), ragged rows / pixels
+    _L(2, 13, 11, 128, 200, 3, p=1, korder=wl.K_CRS, seed=6),   # the paper's flattening: byte transpose of the taps, 2 chunks of 64 channels
+    _L(2, 12, 12, 64, 136, 2, s=2, korder=wl.K_CRS, seed=7),    # 2x2 stride 2 in the paper's flattening
     _L(2, 9, 10, 128, 200, 3, p=1, seed=4),         # K = 1152 bytes: the long-reduction staging (chunks of 512 bytes), 2.25 chunks
     _L(2, 15, 13, 96, 136, 3, s=2, p=1),            # stride 2
     _L(3, 9, 11, 160, 264, 1, korder=wl.K_CRS),     # pointwise, K = 160 (2.5 steps)
@@ -150,7 +152,7 @@ def force_tile():
 
 
 @pytest.mark.parametrize("tile", TILE_IDS)
-@pytest.mark.parametrize("L", SHAPES[:6], ids=lambda L: L.name)
+@pytest.mark.parametrize("L", SHAPES[:8], ids=lambda L: L.name)
 def test_every_tile_shape_matches_oracle(ss, force_tile, L, tile):
     d = wl.make_inputs_q8(L)
     ref = _ref(L, d)
@@ -234,9 +236,15 @@ def test_argument_errors(ss):
             fn()
         return e.value.status
 
-    # channel-slowest flattening with taps, and channel counts that are not a multiple of 16
-    crs = ss.make_desc(L.cout, L.cin, 3, 3, wl.I8, wl.K_CRS)
-    assert status(lambda: ss.ss_conv2d_q8_fwd(crs, x, packed, pad=(1, 1))) == ss.SS_ERR_UNSUPPORTED
+    # channel-slowest flattening with taps other than 3x3 / 2x2, or with cin % 64 != 0; channel counts that are not a
+    # multiple of 16
+    crs5 = ss.make_desc(L.cout, L.cin, 5, 5, wl.I8, wl.K_CRS)
+    p5 = torch.zeros(ss.ss_packed_bytes(crs5), dtype=torch.uint8, device="cuda")
+    assert status(lambda: ss.ss_conv2d_q8_fwd(crs5, x, p5, pad=(2, 2))) == ss.SS_ERR_UNSUPPORTED
+    crs48 = ss.make_desc(64, 48, 3, 3, wl.I8, wl.K_CRS)
+    x48 = torch.zeros((1, 8, 8, 48), dtype=torch.int8, device="cuda")
+    p48 = torch.zeros(ss.ss_packed_bytes(crs48), dtype=torch.uint8, device="cuda")
+    assert status(lambda: ss.ss_conv2d_q8_fwd(crs48, x48, p48, pad=(1, 1))) == ss.SS_ERR_UNSUPPORTED
     d8 = ss.make_desc(64, 8, 1, 1, wl.I8, wl.K_CRS)
     x8 = torch.zeros((1, 4, 4, 8), dtype=torch.int8, device="cuda")
     p8 = torch.zeros(ss.ss_packed_bytes(d8), dtype=torch.uint8, device="cuda")
