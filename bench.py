@@ -91,10 +91,11 @@ class Q8Run:
     for timing (weights ~ N(0, 40) and activations ReLU(N(0, 32)), clipped and cast; random 2:4 patterns; a
     per-channel scale)."""
 
-    def __init__(self, L, torch, ss, wl, dtype=None):
+    def __init__(self, L, torch, ss, wl, dtype=None, korder=None):
         self.L = L
         dtype = ss.SS_I8 if dtype is None else dtype
-        korder = wl.K_RSC if L.kh * L.kw > 1 else L.korder
+        if korder is None:
+            korder = wl.K_RSC if L.kh * L.kw > 1 else L.korder
         self.desc = ss.make_desc(L.cout, L.cin, L.kh, L.kw, dtype, korder)
         g = torch.Generator(device="cuda").manual_seed(L.seed)
 
@@ -118,10 +119,10 @@ class Q8Run:
         self.keep = (W, M, x)
 
 
-def q8_point(torch, ss, wl, L, steps, warmup, reps=3, dtype=None):
+def q8_point(torch, ss, wl, L, steps, warmup, reps=3, dtype=None, korder=None):
     """Sparse / dense-twin time of the 8-bit variant of a layer and its rate in dense-equivalent TOP/s (the published
     dense peaks of int8 and fp8 are the same, 5.0 P/s, so one sparse peak serves both)."""
-    run = Q8Run(L, torch, ss, wl, dtype)
+    run = Q8Run(L, torch, ss, wl, dtype, korder)
     ts = median_time(torch, run.sparse, steps, warmup, reps=reps)
     td = median_time(torch, run.densef, steps, warmup, reps=reps)
     tops = L.dense_equiv_flop / ts / 1e9
@@ -147,6 +148,11 @@ def print_q8_table(torch, ss, wl, steps, warmup):
         del run16
         print(f"{L.name:34s} {L.N:4d} {r['sparse_us']:9.1f} {r['dense_twin_us']:9.1f} {r['speedup']:5.2f} {r['tops']:8.0f} "
               f"{t16:10.1f} {t16 / r['sparse_us']:9.2f} {rf['sparse_us']:8.1f} {rf['dense_twin_us']:8.1f} {rf['speedup']:5.2f}", flush=True)
+        if i < 3:       # the benchmark layer in the paper's own flattening (taps inside a block: byte transpose)
+            rc = q8_point(torch, ss, wl, L, steps, warmup, korder=wl.K_CRS)
+            rfc = q8_point(torch, ss, wl, L, steps, warmup, dtype=ss.SS_F8, korder=wl.K_CRS)
+            print(f"{'  ... channel-slowest flattening':34s} {L.N:4d} {rc['sparse_us']:9.1f} {rc['dense_twin_us']:9.1f} {rc['speedup']:5.2f} "
+                  f"{rc['tops']:8.0f} {'':>10s} {'':>9s} {rfc['sparse_us']:8.1f} {rfc['dense_twin_us']:8.1f} {rfc['speedup']:5.2f}", flush=True)
         if i >= 4:      # the ResNet-50 layers
             tot8 += r["sparse_us"] * L.count
             totd += r["dense_twin_us"] * L.count
@@ -418,11 +424,11 @@ def main():
     te_s = median_time(torch, even.sparse, 20, 3, reps=3)
     te_d = median_time(torch, even.densef, 20, 3, reps=3)
     del even
-    # the 8-bit integer precision point on the same shape (channels-last flattening), N = 32 and N = 500
-    q8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50))
-    q8_big = q8_point(torch, ss, wl, Leven, 20, 3)
-    f8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50), dtype=ss.SS_F8)
-    f8_big = q8_point(torch, ss, wl, Leven, 20, 3, dtype=ss.SS_F8)
+    # the 8-bit precision points on the same shape and flattening, N = 32 and N = 500
+    q8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50), korder=L.korder)
+    q8_big = q8_point(torch, ss, wl, Leven, 20, 3, korder=L.korder)
+    f8_small = q8_point(torch, ss, wl, L, min(args.steps, 200), min(args.warmup, 50), dtype=ss.SS_F8, korder=L.korder)
+    f8_big = q8_point(torch, ss, wl, Leven, 20, 3, dtype=ss.SS_F8, korder=L.korder)
     tc = time_launches(torch, lambda: ss.ss_mask_compress(run.desc, run.W, run.M, packed=run.packed), 20, 3)
     Wu, Uz = run.W.clone(), torch.zeros_like(run.W)     # a zero update: the packed weights stay what they are
     tu = time_launches(torch, lambda: ss.ss_mask_update_compress(run.desc, Wu, Uz, run.M, packed=run.packed), 20, 3)
@@ -444,9 +450,9 @@ def main():
                                      "dense_twin_us": te_d * 1e3, "tflops": Leven.dense_equiv_flop / te_s / 1e9,
                                      "speedup": te_d / te_s,
                                      "frac_sparse_peak": Leven.dense_equiv_flop / te_s / 1e9 / SPARSE_PEAK_TFLOPS},
-        "int8": {"workload": "same shape with int8 operands (channels-last flattening), fp16 output", "n32": q8_small,
+        "int8": {"workload": "same shape, mask and flattening with int8 operands, fp16 output", "n32": q8_small,
                  "n500": q8_big, "peak_tops": SPARSE_INT8_PEAK_TOPS},
-        "fp8": {"workload": "same shape with FP8 E4M3 operands (channels-last flattening), fp16 output", "n32": f8_small,
+        "fp8": {"workload": "same shape, mask and flattening with FP8 E4M3 operands, fp16 output", "n32": f8_small,
                 "n500": f8_big, "peak_tflops": SPARSE_INT8_PEAK_TOPS},
         "compress_us": tc * 1e3, "update_compress_us": tu * 1e3, "eager_launch_us": eager_ms * 1e3,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",

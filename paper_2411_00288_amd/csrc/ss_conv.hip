@@ -97,6 +97,11 @@ __device__ __forceinline__ Acc<DT> mma_sparse(u32x4 a, const B32 &b, Acc<DT> c, 
                                                           (int)idx, 0, 0);
 }
 
+// Which dense FP8 kernels use the 32x32x64 instruction (the others use pairs of 32x32x16, see mma_dense): the deep
+// ones, which have the registers for its 8-register operands, and the short-chunk channels-last staging, whose shallow
+// kernels are otherwise bound by the half-rate instruction (measured: 81 vs 69 us on the N=500 benchmark layer).
+constexpr bool f8_wide(bool deep, int mode) { return deep || mode == 0 /* MODE_VEC */; }
+
 // Dense FP8: one 32x32x64 instruction of the scaled-format family with both formats E4M3 and both block scales
 // 2^0 (exponent byte 127); A and B slots s of lane l are k = 32*(l/32) + s.
 __device__ __forceinline__ f32x16 mma_dense_f8(u32x4 a0, u32x4 a1, const B32 &b, f32x16 c)
@@ -111,7 +116,15 @@ __device__ __forceinline__ Acc<DT> mma_dense(u32x4 a, u32x4 b, Acc<DT> c)
 {
     if constexpr (DT == SS_I8)      // 32x32x32: A lane l slot s <-> k = 16*(l/32) + s, B likewise
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b), c, 0, 0, 0);
-    else if constexpr (DT == SS_F16)
+    else if constexpr (DT == SS_F8) {
+        // Two 32x32x16 FP8 instructions on the low and high 8 bytes (A and B share the lane -> reduction-index map,
+        // and the weight tile was laid out for these very bytes of B).  Half the rate of the 32x32x64 form, but its
+        // operands are register pairs: used by the shallow kernels, which need the occupancy more than the rate.
+        const unsigned long long a0 = a[0] | ((unsigned long long)a[1] << 32), a1 = a[2] | ((unsigned long long)a[3] << 32);
+        const unsigned long long b0 = b[0] | ((unsigned long long)b[1] << 32), b1 = b[2] | ((unsigned long long)b[3] << 32);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8((long)a0, (long)b0, c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8((long)a1, (long)b1, c, 0, 0, 0);
+    } else if constexpr (DT == SS_F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -235,7 +248,7 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // wave's matrix instructions.
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC>
 __global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
-__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : ((DT == SS_F8 && !SPARSE) ? 2 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8)))))   // (the dense FP8 instruction wants its 32-byte A operand in 8 consecutive registers: more pressure)
+__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : ((DT == SS_F8 && !SPARSE && MODE == MODE_VEC && TM * TN == 2) ? 3 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8)))))
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
@@ -642,7 +655,7 @@ void conv_kernel(ConvParams p)
                     for (int tn = 0; tn < TN; tn++) {
                         if constexpr (SPARSE) {
                             acc[tm][tn] = mma_sparse<DT>(as.v[0][tm], b[s % BD][tn], acc[tm][tn], as.idx[tm] >> idx_shift);
-                        } else if constexpr (DT == SS_F8) {
+                        } else if constexpr (DT == SS_F8 && f8_wide(DEEP, MODE)) {
                             acc[tm][tn] = mma_dense_f8(as.v[0][tm], as.v[1][tm], b[s % BD][tn], acc[tm][tn]);
                         } else {
                             acc[tm][tn] = mma_dense<DT>(as.v[0][tm], b[s % BD][tn].lo, acc[tm][tn]);
@@ -652,7 +665,7 @@ void conv_kernel(ConvParams p)
                 // Scheduling: left alone, the compiler sinks every load to just before its first use and the
                 // prefetch distance collapses to zero.  Pin this step's instructions to the step (barriers at both
                 // ends) and interleave the loads for later steps between its matrix instructions.
-                constexpr int NMMA = TM * TN * ((SPARSE || DT == SS_F8) ? 1 : 2);
+                constexpr int NMMA = TM * TN * (SPARSE ? 1 : (DT == SS_F8 ? (f8_wide(DEEP, MODE) ? 1 : 4) : 2));
                 constexpr int DSR = (2 * TN + NMMA - 1) / NMMA;
                 constexpr int VMR = (TM * 2 + NMMA - 1) / NMMA;
 #pragma unroll
@@ -907,7 +920,11 @@ static int pick_tile(const ConvParams &p, hipStream_t s)
     }
     constexpr bool pointwise = MODE == MODE_PW || MODE == MODE_PW2;
     constexpr bool bigchunk = (MODE == MODE_TAPS && KH * KW > 4) || MODE == MODE_VEC8;
-    return launch_tile<DT, SPARSE, MODE, KH, KW>(choose_tile(p, pointwise, bigchunk), p, s);
+    int id = choose_tile(p, pointwise, bigchunk);
+    // The dense FP8 instruction of the deep kernels wants its 32-byte A operand in eight consecutive registers; the
+    // 256x64 four-wave tile then runs at one wave per SIMD (measured 40 % slower than with producer waves).
+    if (DT == SS_F8 && !SPARSE && id == 3) id = 5;
+    return launch_tile<DT, SPARSE, MODE, KH, KW>(id, p, s);
 }
 
 // Channels-last flattening with taps: chunks of 256 reduction indices (a quarter of the barriers, four times the
