@@ -268,7 +268,7 @@ def print_table(torch, ss, wl, steps, warmup, cold, only=""):
             print(f"{L.name:34s} {L.count:2d} {r['gflop']:8.2f} {r.get('sparse_us', float('nan')):10.2f} {r['dense_us']:9.2f} "
                   f"{r.get('speedup', float('nan')):7.2f} {r['tflops']:8.1f} {r['gbs']:7.0f} {r['t_floor_us']:8.2f} {r['t_floor_us'] / t_used:5.2f}", flush=True)
         print(f"{'total (x count)':34s}    {'':8s} {tot_s:10.1f} {tot_d:9.1f} {tot_d / tot_s:7.2f} {'':8s} {'':7s} {tot_f:8.1f} {tot_f / tot_s:5.2f}", flush=True)
-        if "ConvNeXt" in title and not only:
+        if "ConvNeXt" in title and (not only or only in "cnx_dw_7x7_96"):
             # the block's grouped convolution stays dense in the paper and runs through the dedicated depthwise kernel
             N, H, C = layers[0].N, layers[0].H, 96
             x = torch.randn((N, H, H, C), device="cuda").to(torch.bfloat16)
