@@ -59,7 +59,7 @@ struct ConvParams {
     int tiles_m;
     unsigned x_bytes, a_bytes, meta_bytes;
     // division by Ho*Wo, Wo and tiles_m as multiply + shift (see fast_div)
-    unsigned howo_mul, howo_sh, wo_mul, wo_sh, tm_mul, tm_sh;
+    unsigned howo_mul, howo_sh, wo_mul, wo_sh, tm_mul, tm_sh, cin_mul, cin_sh, kw_mul, kw_sh;
 };
 
 // floor(n / d) for 0 <= n < 2^31 as (n * mul) >> sh with s = ceil(log2 d), sh = 31 + s, mul = ceil(2^sh / d):
@@ -174,6 +174,10 @@ __device__ __forceinline__ float normal_cdf(float v)
 //               reduction and the chunk's channel offset travels in the load's scalar offset.
 //               Chunks of 128 reduction indices (MODE_PW) or 64 (MODE_PW2, for very short reductions).
 //   MODE_GATHER any flattening / shape: one 16-bit load per element (slow, general fallback).
+//   MODE_GATHER4 channels-last flattening with cin % 4 == 0 (e.g. an image padded from 3 to 4 channels, the
+//               column-wise augmentation Sec. 3.3 suggests for reductions that are no multiple of 4): every
+//               aligned run of 4 reduction indices is 8 contiguous, 8-byte aligned bytes of one pixel: one 8-byte
+//               load per 2:4 block.
 //   MODE_TAPS   the paper's flattening (channel slowest) with a KH x KW kernel and cin % 32 == 0:
 //               a 2:4 block then holds 4 consecutive (channel, tap) pairs, i.e. activations of
 //               different pixels.  A thread loads, for one output pixel and 8 channels, the
@@ -181,7 +185,7 @@ __device__ __forceinline__ float normal_cdf(float v)
 //               channel-major order before the LDS write, so the MFMA side still reads 16-byte
 //               vectors.  A chunk is 32 channels = KH*KW reduction steps.  (8-bit operands: 16 channels per
 //               vector, a byte transpose, chunks of 64 channels.)
-enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2, MODE_PW = 3, MODE_PW2 = 4, MODE_VEC8 = 5 };
+enum { MODE_VEC = 0, MODE_GATHER = 1, MODE_TAPS = 2, MODE_PW = 3, MODE_PW2 = 4, MODE_VEC8 = 5, MODE_GATHER4 = 6 };
 constexpr bool is_vec(int mode) { return mode == MODE_VEC || mode == MODE_VEC8; }
 
 // Weight fragments of one 32-wide reduction step for the TM row tiles of a wave.
@@ -255,7 +259,7 @@ void conv_kernel(ConvParams p)
     static_assert(!SPEC || DEEP, "producer waves come with the deep variant only");
     constexpr bool Q8 = is_byte_type(DT);                 // 8-bit operands: staged as byte pairs, full index words, scaled tail
     constexpr int ODT = out_type<DT>();
-    static_assert(!Q8 || MODE != MODE_GATHER, "8-bit operands travel in 16-byte runs only");
+    static_assert(!Q8 || (MODE != MODE_GATHER && MODE != MODE_GATHER4), "8-bit operands travel in 16-byte runs only");
     constexpr int NMATH = WAVES_M * WAVES_N * 64;         // threads that multiply
     constexpr int NT = NMATH + (SPEC ? 256 : 0);
     constexpr int BM = WAVES_M * TM * 32;
@@ -319,7 +323,7 @@ void conv_kernel(ConvParams p)
 
     // ------------------------------------------------------------------ activation staging state
     // per pixel row and chunk: 16-byte runs (VEC: 8, TAPS: 4 channel octets) or 4-element blocks (GATHER: 16)
-    constexpr int UNITS = (MODE == MODE_GATHER) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_VEC8 ? 32 : (MODE == MODE_PW ? 16 : 8)));
+    constexpr int UNITS = (MODE == MODE_GATHER || MODE == MODE_GATHER4) ? 16 : (MODE == MODE_TAPS ? 4 : (MODE == MODE_VEC8 ? 32 : (MODE == MODE_PW ? 16 : 8)));
     constexpr int ST = SPEC ? (256 < BN * UNITS ? 256 : BN * UNITS) : (NT < BN * UNITS ? NT : BN * UNITS);     // staging threads (whole waves); the rest only multiply
     constexpr int ITEMS = BN * UNITS / ST;
     constexpr int NSET = SPEC ? 2 : 1;                    // producer waves hold two chunks in registers
@@ -389,6 +393,7 @@ void conv_kernel(ConvParams p)
 
     u32x4 stage_v_[NSET][(is_vec(MODE) || MODE == MODE_PW || MODE == MODE_PW2) ? ITEMS : 1];
     uint16_t stage_g_[NSET][MODE == MODE_GATHER ? ITEMS : 1][4];
+    uint2 stage_g4_[NSET][MODE == MODE_GATHER4 ? ITEMS : 1];
     u32x4 stage_t_[NSET][MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
     auto stage_load = [&](int ci, int set = 0) {      // set: compile time at every call site
@@ -416,6 +421,21 @@ void conv_kernel(ConvParams p)
 #pragma unroll
             for (int i = 0; i < ITEMS; i++)
                 stage_v[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(kok ? pwoff[i] : kOutOfRange), ci * (BK * 2), 0);
+        } else if constexpr (MODE == MODE_GATHER4) {
+            // this thread's block of 4 reduction indices: one tap, 4 consecutive channels
+            auto &stage_g4 = stage_g4_[set];
+            const int k0 = ci * BK + unit * 4;
+            const int tap = fast_div(k0, p.cin_mul, p.cin_sh);
+            const int c = k0 - tap * p.Cin;
+            const int r = fast_div(tap, p.kw_mul, p.kw_sh);
+            const int t = tap - r * p.kw;
+            const unsigned koff = k0 < p.K ? (unsigned)(((r * p.W + t) * p.Cin + c) * 2) : kOutOfRange;
+#pragma unroll
+            for (int i = 0; i < ITEMS; i++) {
+                int ih = ih0[i] + r, iw = iw0[i] + t;
+                bool ok = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W && koff != kOutOfRange;
+                stage_g4[i] = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? pixbyte[i] + koff : kOutOfRange), 0, 0));
+            }
         } else if constexpr (MODE == MODE_GATHER) {
             unsigned off[4];
             int er[4], et[4];
@@ -512,7 +532,9 @@ void conv_kernel(ConvParams p)
                 }
             } else {
                 if (i < j * ITEMS / n || i >= (j + 1) * ITEMS / n) continue;
-                if constexpr (MODE == MODE_GATHER) {
+                if constexpr (MODE == MODE_GATHER4) {
+                    *reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * 4) = stage_g4_[set][i];
+                } else if constexpr (MODE == MODE_GATHER) {
                     uint2 v = make_uint2((uint32_t)stage_g[i][0] | ((uint32_t)stage_g[i][1] << 16),
                                          (uint32_t)stage_g[i][2] | ((uint32_t)stage_g[i][3] << 16));
                     *reinterpret_cast<uint2 *>(Bs + pr * ROW + unit * 4) = v;
@@ -959,6 +981,7 @@ static int pick_mode(const ss_weight_desc *desc, const ConvParams &p, hipStream_
         if (desc->kh == 3 && desc->kw == 3) return pick_tile<DT, SPARSE, MODE_TAPS, 3, 3>(p, s);
         if (desc->kh == 2 && desc->kw == 2) return pick_tile<DT, SPARSE, MODE_TAPS, 2, 2>(p, s);
     }
+    if (desc->cin % 4 == 0 && desc->korder == SS_K_RSC) return pick_tile<DT, SPARSE, MODE_GATHER4, 1, 1>(p, s);
     return pick_tile<DT, SPARSE, MODE_GATHER, 1, 1>(p, s);
     }
 }
@@ -1022,6 +1045,8 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.tm_mul = p.tm_sh = 0;
     fast_div_setup((unsigned)(Ho * Wo), &p.howo_mul, &p.howo_sh);
     fast_div_setup((unsigned)Wo, &p.wo_mul, &p.wo_sh);
+    fast_div_setup((unsigned)p.Cin, &p.cin_mul, &p.cin_sh);
+    fast_div_setup((unsigned)p.kw, &p.kw_mul, &p.kw_sh);
     p.x_bytes = (unsigned)xbytes;
     p.a_bytes = (unsigned)((size_t)t.Mt * t.Ks * (SPARSE ? 1024 : 2048));
     p.meta_bytes = SPARSE ? (unsigned)((size_t)t.Mt * t.Kp * 256) : 4u;

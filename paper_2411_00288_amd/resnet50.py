@@ -2,7 +2,10 @@
 dataflow: 7x7 stem -> max pool -> 16 bottleneck blocks, every block closed by the fused add + ReLU tail.
 
 48 of the 53 convolutions carry a 2:4 mask and run on the sparse path (or, with ``sparse=False``, on the dense twin
-with the same masked weights); the stem (K = 147) and the four shortcut convolutions stay dense, as in the paper.
+with the same masked weights); the stem and the four shortcut convolutions stay dense.  The image is handed over with
+a fourth, all-zero channel (the column-wise augmentation that Sec. 3.3 suggests for a reduction length that is no
+multiple of 4: K = 7*7*4 = 196 instead of 147), so that every pixel is 8 aligned bytes and the stem's staging loads
+one whole 2:4 block at a time; ``image_channels=3`` keeps the unpadded form.
 Batch norm is folded into the bias.  Weights, masks and biases are synthetic (``workloads``); this module only wires
 buffers and launches -- every arithmetic step runs in the library's kernels.
 """
@@ -29,10 +32,10 @@ class Op:
     residual: int | None = None
 
 
-def build_ops(batch: int, image: int, dtype: int = wl.BF16, seed: int = 7000):
+def build_ops(batch: int, image: int, dtype: int = wl.BF16, seed: int = 7000, image_channels: int = 4):
     """The op list and the activation shapes {buffer id: (N, H, W, C)}."""
     ops: list[Op] = []
-    shapes = {0: (batch, image, image, 3)}
+    shapes = {0: (batch, image, image, image_channels)}
     nxt = [1]
 
     def new_buf(shape):
@@ -41,15 +44,16 @@ def build_ops(batch: int, image: int, dtype: int = wl.BF16, seed: int = 7000):
         shapes[i] = shape
         return i
 
-    def conv(name, src, cout, k, stride, act, mask, residual=None, relu_input=True):
+    def conv(name, src, cout, k, stride, act, mask, residual=None, relu_input=True, korder=wl.K_CRS):
         N, H, W, C = shapes[src]
         L = wl.Layer(name, N=N, H=H, W=W, cin=C, cout=cout, kh=k, kw=k, stride=stride, pad=k // 2, dtype=dtype, act=act,
-                     mask=mask, relu_input=relu_input, seed=seed + len(ops))
+                     korder=korder, mask=mask, relu_input=relu_input, seed=seed + len(ops))
         dst = new_buf((N, L.Ho, L.Wo, cout))
         ops.append(Op("conv", name, src, dst, L, residual))
         return dst
 
-    a = conv("stem", 0, 64, 7, 2, wl.ACT_RELU, "none", relu_input=False)
+    a = conv("stem", 0, 64, 7, 2, wl.ACT_RELU, "none", relu_input=False,
+             korder=wl.K_RSC if image_channels % 4 == 0 else wl.K_CRS)
     N, H, W, C = shapes[a]
     p = new_buf((N, (H + 2 - 3) // 2 + 1, (W + 2 - 3) // 2 + 1, C))
     ops.append(Op("pool", "maxpool", a, p))
@@ -69,8 +73,8 @@ class Trunk:
     on the current stream (capturable in a HIP graph)."""
 
     def __init__(self, batch: int, image: int = 224, dtype: int = wl.BF16, sparse: bool = True, seed: int = 7000,
-                 c3_scale: float = 0.25, keep_host: bool = False):
-        self.ops, self.shapes = build_ops(batch, image, dtype, seed)
+                 c3_scale: float = 0.25, keep_host: bool = False, image_channels: int = 4):
+        self.ops, self.shapes = build_ops(batch, image, dtype, seed, image_channels)
         self.dtype, self.sparse = dtype, sparse
         tdt = ss.torch_dtype(dtype)
         self.bufs = {i: torch.zeros(shp, dtype=tdt, device="cuda") for i, shp in self.shapes.items()}
@@ -111,4 +115,10 @@ class Trunk:
         return self.output
 
     def dense_equiv_flop(self) -> float:
-        return float(sum(op.layer.dense_equiv_flop for op in self.ops if op.kind == "conv"))
+        """Dense-equivalent FLOP of one forward pass; the stem counts its three real channels, not the padding."""
+        total = 0.0
+        for op in self.ops:
+            if op.kind == "conv":
+                f = op.layer.dense_equiv_flop
+                total += f * 3 / op.layer.cin if op.name == "stem" else f
+        return total

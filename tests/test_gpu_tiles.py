@@ -32,6 +32,8 @@ SHAPES = [
     _L(2, 9, 9, 24, 140, 3, p=1, korder=wl.K_RSC),         # channels-last flattening with taps
     _L(2, 9, 9, 64, 140, 3, p=1, korder=wl.K_RSC, seed=5), # channels-last flattening, K = 576: chunks of 256 (2.25 of them)
     _L(1, 11, 9, 12, 150, 3, p=1),                         # gather fallback (cin % 32 != 0)
+    _L(2, 19, 17, 4, 70, 7, s=2, p=3, korder=wl.K_RSC, seed=9),   # 4-channel image, 7x7 stride 2: one 8-byte load per block, K = 196
+    _L(1, 9, 10, 20, 150, 3, p=1, korder=wl.K_RSC, seed=8),       # cin % 8 == 4 in the channels-last flattening
     _L(2, 14, 14, 192, 260, 3, p=1, seed=3),               # six chunks of 32 channels
 ]
 

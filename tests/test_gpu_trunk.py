@@ -18,13 +18,15 @@ def _conv_ref(L, d, x_bits, res_bits):
                          bias=d["bias"], stride=(L.stride,) * 2, pad=(L.pad,) * 2, act=L.act, residual=res_bits)
 
 
-@pytest.mark.parametrize("sparse", [True, False])
-def test_trunk_ops_match_oracle_on_their_actual_inputs(ss, sparse):
+@pytest.mark.parametrize("sparse,channels", [(True, 4), (False, 4), (True, 3)])
+def test_trunk_ops_match_oracle_on_their_actual_inputs(ss, sparse, channels):
     from paper_2411_00288_amd import resnet50
-    t = resnet50.Trunk(batch=1, image=64, dtype=wl.BF16, sparse=sparse, keep_host=True)
+    t = resnet50.Trunk(batch=1, image=64, dtype=wl.BF16, sparse=sparse, keep_host=True, image_channels=channels)
     assert sum(op.kind == "conv" for op in t.ops) == 53 and t.output.shape == (1, 2, 2, 2048)
     rng = np.random.Generator(np.random.PCG64(77))
-    x_bits = wl.to_bits(rng.standard_normal((1, 64, 64, 3), dtype=np.float32), wl.BF16)
+    x = rng.standard_normal((1, 64, 64, channels), dtype=np.float32)
+    x[..., 3:] = 0                                              # the padding channel of the image
+    x_bits = wl.to_bits(x, wl.BF16)
     t.input.copy_(torch.from_numpy(x_bits.view(np.int16)).cuda().view(torch.bfloat16))
     t.forward()
     torch.cuda.synchronize()
