@@ -23,6 +23,7 @@
 // the zero padding, past the last pixel or past the reduction length presents an offset beyond the
 // buffer's size and the hardware returns 0 -- no branches, no selects.
 #include "ss_internal.h"
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -862,12 +863,17 @@ static int launch(const ConvParams &p0, hipStream_t s)
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
     auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, SPEC>;
     if (smem_res > 64 * 1024) {
-        static bool attr_set = false;    // once per process: raises this kernel's dynamic-LDS limit
-        if (!attr_set) {
+        // Raises this kernel's dynamic-LDS limit, once per device (the attribute belongs to the device's copy of the
+        // kernel).  Two threads racing here both set it: harmless.
+        static std::atomic<unsigned long long> done_mask{0};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return SS_ERR_HIP;
+        const unsigned long long bit = 1ull << (dev & 63);
+        if (dev >= 64 || !(done_mask.load(std::memory_order_acquire) & bit)) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)smem_res) != hipSuccess)
                 return SS_ERR_HIP;
-            attr_set = true;
+            if (dev < 64) done_mask.fetch_or(bit, std::memory_order_release);
         }
     }
     kern<<<dim3((unsigned)blocks), dim3((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64), smem, s>>>(p);
@@ -957,7 +963,8 @@ template <int DT, bool SPARSE>
 static int pick_vec(const ConvParams &p, hipStream_t s)
 {
     if (p.K >= 512) {
-        const int id = getenv("SS_TILE") ? atoi(getenv("SS_TILE")) : choose_tile(p, false, true);
+        const char *env = getenv("SS_TILE");
+        const int id = env ? atoi(env) : choose_tile(p, false, true);
         if (id == 4 || id == 5 || (id == 3 && !is_byte_type(DT))) return pick_tile<DT, SPARSE, MODE_VEC8, 1, 1>(p, s);
     }
     return pick_tile<DT, SPARSE, MODE_VEC, 1, 1>(p, s);
