@@ -219,6 +219,35 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
                             void *y, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Two masked convolutions in one kernel: a k x k convolution (k > 1) whose every output channel fits one tile,
+ * followed by a 1x1 convolution on its output -- the 3x3 -> 1x1 expansion that closes a ResNet bottleneck:
+ *     t = act1( conv_kxk(x; W1) + bias1 )          rounded to the 16-bit type, exactly as ss_conv2d_fwd would store it
+ *     y = act2( conv_1x1(t; W2) + bias2 + residual ) = what ss_conv2d_res_fwd would compute from t
+ * The intermediate t never leaves the compute unit's LDS, which saves its write and read (the results are those
+ * of the two separate calls up to the order of the fp32 additions in the second one).
+ *   desc1   the k x k layer: 16-bit dtype, cout % 32 == 0, cout <= 256, and either SS_K_CRS with a 3x3 kernel and
+ *           cin % 32 == 0, or SS_K_RSC with cin % 8 == 0 -- otherwise SS_ERR_UNSUPPORTED
+ *   desc2   the 1x1 layer: same dtype, cin == desc1->cout, cout % 32 == 0
+ *   packed1, packed2   written by ss_mask_compress for desc1 / desc2                         (read only)
+ *   bias1   [desc1->cout] fp32 or NULL; bias2 [desc2->cout] fp32, 16-byte aligned, or NULL     (read only)
+ *   residual [N][Ho][Wo][desc2->cout] 16-bit, 16-byte aligned, or NULL; may alias y            (read only)
+ *   y       [N][Ho][Wo][desc2->cout], Ho / Wo from the k x k layer's stride and padding        (written)
+ * Asynchronous on `stream`.
+ */
+int ss_conv2d_pw_fused_fwd(const ss_weight_desc *desc1, const void *x, int32_t N, int32_t H, int32_t Wd,
+                           const void *packed1, const float *bias1,
+                           int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act1,
+                           const ss_weight_desc *desc2, const void *packed2, const float *bias2,
+                           const void *residual, int32_t act2, void *y, void *stream);
+
+/* The dense twin of ss_conv2d_pw_fused_fwd (operands built by ss_dense_pack). */
+int ss_conv2d_pw_fused_dense_fwd(const ss_weight_desc *desc1, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                 const void *dense1, const float *bias1,
+                                 int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act1,
+                                 const ss_weight_desc *desc2, const void *dense2, const float *bias2,
+                                 const void *residual, int32_t act2, void *y, void *stream);
+
+/*
  * The masked convolution on 8-bit operands: Eq. (6) with every product and the running sum exact in
  * int32 (SS_I8), or with exact products summed in fp32 (SS_F8), followed by the dequantising layer tail
  *     y[n,ho,wo,o] = act( scale[o] * sum_k (M (.) W)[o,k] * U(X)[k,p] + bias[o] ),

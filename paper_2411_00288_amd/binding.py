@@ -23,7 +23,7 @@ SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
-           "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd"]
+           "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd"]
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -66,6 +66,9 @@ def _load() -> ctypes.CDLL:
     q8_args = [dp, vp, i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ss_conv2d_q8_fwd.argtypes = q8_args
     lib.ss_conv2d_q8_dense_fwd.argtypes = q8_args
+    fused_args = [dp, vp, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, dp, vp, vp, vp, i32, vp, vp]
+    lib.ss_conv2d_pw_fused_fwd.argtypes = fused_args
+    lib.ss_conv2d_pw_fused_dense_fwd.argtypes = fused_args
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -353,6 +356,55 @@ def ss_conv2d_q8_dense_fwd(desc, x, dense, scale=None, bias=None, stride=(1, 1),
     st = _lib.ss_conv2d_q8_dense_fwd(*args, _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_conv2d_q8_dense_fwd")
+    return y
+
+
+def prepare_conv2d_pw_fused(desc1, x, w1, bias1, stride, pad, act1, desc2, w2, bias2=None, residual=None,
+                            act2=SS_ACT_NONE, y=None, sparse=True):
+    """Marshal the arguments of ss_conv2d_pw_fused_fwd / ss_conv2d_pw_fused_dense_fwd once; returns (launch, y)."""
+    what = "ss_conv2d_pw_fused_fwd" if sparse else "ss_conv2d_pw_fused_dense_fwd"
+    if x is None or x.dim() != 4 or x.shape[3] != desc1.cin:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
+    N, H, W, _ = x.shape
+    shp1 = out_shape(desc1, N, H, W, stride, pad)
+    if shp1[1] <= 0 or shp1[2] <= 0:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")
+    shp = (N, shp1[1], shp1[2], desc2.cout)
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != shp or y.dtype != x.dtype:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: y must be {shp} {x.dtype}")
+    if residual is not None and (tuple(residual.shape) != shp or residual.dtype != x.dtype or not residual.is_contiguous()):
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: residual must be contiguous {shp} {x.dtype}")
+    fn = getattr(_lib, what)
+    args = (ctypes.byref(desc1), _dev_ptr(x, "x", (torch_dtype(desc1.dtype),)), N, H, W, _dev_ptr(w1, "weights 1"),
+            _dev_ptr(bias1, "bias1", (torch.float32,), allow_none=True), stride[0], stride[1], pad[0], pad[1], act1,
+            ctypes.byref(desc2), _dev_ptr(w2, "weights 2"), _dev_ptr(bias2, "bias2", (torch.float32,), allow_none=True),
+            _dev_ptr(residual, "residual", allow_none=True), act2, _dev_ptr(y, "y"))
+    keep = (desc1, desc2, x, w1, w2, bias1, bias2, residual, y)
+
+    def launch(_keep=keep):
+        st = fn(*args, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if st != SS_OK:
+            raise SSError(st, what)
+    return launch, y
+
+
+def ss_conv2d_pw_fused_fwd(desc1, x, packed1, bias1, stride, pad, act1, desc2, packed2, bias2=None, residual=None,
+                           act2=SS_ACT_NONE, y=None) -> torch.Tensor:
+    """k x k masked convolution followed by a 1x1 masked convolution (+ residual), the intermediate kept on chip."""
+    launch, y = prepare_conv2d_pw_fused(desc1, x, packed1, bias1, stride, pad, act1, desc2, packed2, bias2, residual,
+                                        act2, y, sparse=True)
+    launch()
+    return y
+
+
+def ss_conv2d_pw_fused_dense_fwd(desc1, x, dense1, bias1, stride, pad, act1, desc2, dense2, bias2=None, residual=None,
+                                 act2=SS_ACT_NONE, y=None) -> torch.Tensor:
+    """The dense twin of ss_conv2d_pw_fused_fwd."""
+    launch, y = prepare_conv2d_pw_fused(desc1, x, dense1, bias1, stride, pad, act1, desc2, dense2, bias2, residual,
+                                        act2, y, sparse=False)
+    launch()
     return y
 
 

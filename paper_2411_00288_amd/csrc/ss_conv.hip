@@ -61,6 +61,14 @@ struct ConvParams {
     unsigned x_bytes, a_bytes, meta_bytes;
     // division by Ho*Wo, Wo and tiles_m as multiply + shift (see fast_div)
     unsigned howo_mul, howo_sh, wo_mul, wo_sh, tm_mul, tm_sh, cin_mul, cin_sh, kw_mul, kw_sh;
+    // fused second contraction (a 1x1 convolution on this convolution's output tile)
+    const uint8_t *a2_vals;
+    const uint32_t *a2_meta;
+    const float *bias2;
+    const uint16_t *res2;     // [P][Cout2] or nullptr
+    uint16_t *y2;             // [P][Cout2]
+    int Cout2, Ks2, Kp2, Mt2, act2;
+    unsigned a2_bytes, meta2_bytes;
 };
 
 // floor(n / d) for 0 <= n < 2^31 as (n * mul) >> sh with s = ceil(log2 d), sh = 31 + s, mul = ceil(2^sh / d):
@@ -223,18 +231,22 @@ constexpr int ring_size(int ksteps, int regs_per_step, int budget)
 
 // LDS of a workgroup: the staging buffers, reused by the epilogue for the output tile (16-bit, or fp32 when a
 // residual is added after it), followed by the tile's bias values (fp32).
+// Fused second contraction: every wave owns a staging region of 32 pixels x (32 + 4) floats behind the 16-bit tile.
+constexpr int kFuseRow = 32 + 4;
+constexpr size_t kFuseRegion = 32 * kFuseRow * 4;
+
 template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
-constexpr size_t smem_body(bool with_residual)
+constexpr size_t smem_body(bool with_residual, int fuse_waves = 0)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
     size_t stage = (size_t)CS::NBUF * BN * CS::ROW * 2;
-    size_t epi = with_residual ? (size_t)BN * (BM + 4) * 4 : (size_t)BN * (BM * 2 + 8);
+    size_t epi = with_residual ? (size_t)BN * (BM + 4) * 4 : (size_t)BN * (BM * 2 + 8) + (size_t)fuse_waves * kFuseRegion;
     return stage > epi ? stage : epi;
 }
 template <int BM, int BN, int MODE, int KH, int KW, bool DEEP>
-constexpr size_t smem_bytes(bool with_residual)
+constexpr size_t smem_bytes(bool with_residual, int fuse_waves = 0)
 {
-    return smem_body<BM, BN, MODE, KH, KW, DEEP>(with_residual) + (size_t)BM * 4;
+    return smem_body<BM, BN, MODE, KH, KW, DEEP>(with_residual, fuse_waves) + (size_t)BM * 4;
 }
 
 // Waves per SIMD the register allocator must leave room for: small wave tiles are latency-bound
@@ -251,7 +263,11 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // transposes, LDS writes); the WAVES_M x WAVES_N waves only fetch weights, read LDS and multiply.
 // A wave issues in order, so without this split every wait of the staging code also stalls the
 // wave's matrix instructions.
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC>
+// FUSE: the tile (all output channels of this convolution for BN pixels, bias and activation applied, rounded to
+// 16 bit exactly as it would be stored) stays in LDS and is at once the activation operand of a following 1x1
+// convolution, whose output (+ bias + residual, activation) is what the kernel writes: the 3x3 -> 1x1 expansion of a
+// bottleneck without the intermediate tensor's round trip through memory.
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC, bool FUSE = false>
 __global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
 __attribute__((amdgpu_waves_per_eu(DEEP ? 1 : ((DT == SS_F8 && !SPARSE && MODE == MODE_VEC && TM * TN == 2) ? 3 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8)))))
 void conv_kernel(ConvParams p)
@@ -305,9 +321,11 @@ void conv_kernel(ConvParams p)
 
     // The tile's bias values are fetched now and parked in LDS after the first staging store, so the
     // epilogue does not pay a global-memory round trip.
-    const bool with_res = !Q8 && p.residual != nullptr;     // uniform
+    static_assert(!FUSE || !Q8, "the fused second contraction is built for the 16-bit types");
+    const bool with_res = !Q8 && !FUSE && p.residual != nullptr;     // uniform (fused: the residual belongs to the second layer)
     float *bias_s = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) +
-                                              (with_res ? smem_body<BM, BN, MODE, KH, KW, DEEP>(true) : smem_body<BM, BN, MODE, KH, KW, DEEP>(false)));
+                                              (with_res ? smem_body<BM, BN, MODE, KH, KW, DEEP>(true)
+                                                        : smem_body<BM, BN, MODE, KH, KW, DEEP>(false, FUSE ? NT / 64 : 0)));
     // (Loaded after the first activation / weight loads are on their way: issued first, its latency would
     // sit in front of everything else.)
     float *scale_s = bias_s + BM;                     // (8-bit operands only)
@@ -757,6 +775,104 @@ void conv_kernel(ConvParams p)
             if (p.act == SS_ACT_GELU) to_lds(gelu); else to_lds(relu_or_id);
         }
         __syncthreads();
+        if constexpr (FUSE) {
+            // ---- second contraction: y2[pixel, o2] = act2( sum_c A2[o2, c] * tile[pixel, c] + bias2[o2] + residual[pixel, o2] )
+            // Every wave (producers included) takes row tiles of 32 output channels in turn; its weights and bias for
+            // the next row tile are fetched while the current one is multiplied.  The fp32 result of 32 pixels x 32
+            // channels crosses the wave's own LDS region so that residual loads and stores are 16-byte runs.
+            constexpr int NW = NT / 64;
+            constexpr int KS2 = BM / 32;                  // upper bound of the second reduction's steps (its length is this convolution's cout)
+            constexpr int TN2 = BN / 32;
+            float *reg = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + (size_t)BN * (BM * 2 + 8)) + wave * (32 * kFuseRow);
+            const __amdgpu_buffer_rsrc_t ra2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a2_vals), 0, (int)p.a2_bytes, kRsrcFlags);
+            const __amdgpu_buffer_rsrc_t rm2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a2_meta), 0, (int)p.meta2_bytes, kRsrcFlags);
+            const int lane2 = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+            const int g2 = lane2 >> 5, c2 = lane2 & 31;
+            const float floor2 = p.act2 == SS_ACT_RELU ? 0.f : -__builtin_inff();
+            struct Row2 {
+                u32x4 v[SPARSE ? 1 : 2][KS2];
+                uint32_t idx[KS2];
+                float4 b[4];
+            };
+            auto load_row = [&](Row2 &r, int mt) {
+#pragma unroll
+                for (int s2 = 0; s2 < KS2; s2++) {
+                    if (s2 >= p.Ks2) break;               // uniform
+                    if constexpr (SPARSE) {
+                        r.v[0][s2] = __builtin_amdgcn_raw_buffer_load_b128(ra2, (int)(((unsigned)(mt * p.Ks2 + s2) * 64 + lane2) * 16u), 0, 0);
+                        r.idx[s2] = __builtin_amdgcn_raw_buffer_load_b32(rm2, (int)(((unsigned)(mt * p.Kp2 + (s2 >> 1)) * 64 + lane2) * 4u), 0, 0);
+                    } else {
+                        const unsigned off = ((unsigned)(mt * p.Ks2 + s2) * 128 + lane2) * 16u;
+                        r.v[0][s2] = __builtin_amdgcn_raw_buffer_load_b128(ra2, (int)off, 0, 0);
+                        r.v[1][s2] = __builtin_amdgcn_raw_buffer_load_b128(ra2, (int)off, 1024, 0);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    r.b[q] = p.bias2 ? *reinterpret_cast<const float4 *>(p.bias2 + mt * 32 + 8 * q + 4 * g2) : make_float4(0.f, 0.f, 0.f, 0.f);
+            };
+            Row2 cur, nxt;
+            if (wave < p.Mt2) load_row(cur, wave);
+            for (int mt = wave; mt < p.Mt2; mt += NW) {
+                if (mt + NW < p.Mt2) load_row(nxt, mt + NW);
+#pragma unroll
+                for (int tn = 0; tn < TN2; tn++) {
+                    f32x16 acc2;
+#pragma unroll
+                    for (int v = 0; v < 16; v++) acc2[v] = 0.f;
+#pragma unroll
+                    for (int s2 = 0; s2 < KS2; s2++) {
+                        if (s2 >= p.Ks2) break;           // uniform
+                        const uint16_t *src = Cs + (tn * 32 + c2) * CROW + 32 * s2 + 16 * g2;     // 8-byte aligned
+                        const uint2 u0 = *reinterpret_cast<const uint2 *>(src), u1 = *reinterpret_cast<const uint2 *>(src + 4);
+                        const uint2 u2 = *reinterpret_cast<const uint2 *>(src + 8), u3 = *reinterpret_cast<const uint2 *>(src + 12);
+                        B32 bf;
+                        bf.lo = u32x4{u0.x, u0.y, u1.x, u1.y};
+                        bf.hi = u32x4{u2.x, u2.y, u3.x, u3.y};
+                        if constexpr (SPARSE) {
+                            acc2 = mma_sparse<DT>(cur.v[0][s2], bf, acc2, cur.idx[s2] >> ((s2 & 1) * 16));
+                        } else {
+                            acc2 = mma_dense<DT>(cur.v[0][s2], bf.lo, acc2);
+                            acc2 = mma_dense<DT>(cur.v[1][s2], bf.hi, acc2);
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; q++)
+                        *reinterpret_cast<float4 *>(reg + c2 * kFuseRow + 8 * q + 4 * g2) =
+                            make_float4(acc2[4 * q + 0] + cur.b[q].x, acc2[4 * q + 1] + cur.b[q].y, acc2[4 * q + 2] + cur.b[q].z, acc2[4 * q + 3] + cur.b[q].w);
+                    // (a wave's LDS operations execute in order: the reads below see the writes above)
+#pragma unroll
+                    for (int j = 0; j < 2; j++) {
+                        const int it = lane2 + 64 * j;
+                        const int px = it >> 2, run = it & 3;
+                        const int pg = n0 + tn * 32 + px, o = mt * 32 + run * 8;
+                        const float4 lo = *reinterpret_cast<const float4 *>(reg + px * kFuseRow + run * 8);
+                        const float4 hi = *reinterpret_cast<const float4 *>(reg + px * kFuseRow + run * 8 + 4);
+                        if (pg >= p.P) continue;
+                        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                        if (p.res2 != nullptr) {
+                            const u32x4 rr = *reinterpret_cast<const u32x4 *>(p.res2 + (size_t)pg * p.Cout2 + o);
+#pragma unroll
+                            for (int e = 0; e < 4; e++) {
+                                v[2 * e] += widen<ODT>((uint16_t)(rr[e] & 0xFFFFu));
+                                v[2 * e + 1] += widen<ODT>((uint16_t)(rr[e] >> 16));
+                            }
+                        }
+                        uint32_t w[4];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) {
+                            float a = v[2 * e], b = v[2 * e + 1];
+                            if (p.act2 == SS_ACT_GELU) { a = gelu(a); b = gelu(b); }
+                            else { a = a < floor2 ? 0.f : a; b = b < floor2 ? 0.f : b; }
+                            w[e] = cvt_pack2<ODT>(a, b);
+                        }
+                        *reinterpret_cast<uint4 *>(p.y2 + (size_t)pg * p.Cout2 + o) = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                }
+                cur = nxt;
+            }
+            return;
+        }
         for (int it = etid; it < BN * RUNS; it += NT) {
             const int pl = it / RUNS, run = it % RUNS;
             const int pg = n0 + pl, o = m0 + run * 8;
@@ -846,22 +962,24 @@ void conv_kernel(ConvParams p)
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false, bool SPEC = false>
+template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false, bool SPEC = false, bool FUSE = false>
 static int launch(const ConvParams &p0, hipStream_t s)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+    constexpr int NWAVES = WAVES_M * WAVES_N + (SPEC ? 4 : 0);
     constexpr size_t scale_bytes = is_byte_type(DT) ? (size_t)BM * 4 : 0;      // the per-channel scales sit behind the bias values
-    constexpr size_t smem_plain = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(false) + scale_bytes;
-    constexpr size_t smem_res = is_byte_type(DT) ? smem_plain : smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
+    constexpr size_t smem_plain = smem_bytes<BM, BN, MODE, KH, KW, DEEP>(false, FUSE ? NWAVES : 0) + scale_bytes;
+    constexpr size_t smem_res = (is_byte_type(DT) || FUSE) ? smem_plain : smem_bytes<BM, BN, MODE, KH, KW, DEEP>(true);
     static_assert(smem_plain <= 160 * 1024 && smem_res <= 160 * 1024, "LDS tile too large");
-    const size_t smem = p0.residual ? smem_res : smem_plain;
+    const size_t smem = (p0.residual && !FUSE) ? smem_res : smem_plain;
+    if (FUSE && (p0.Cout > BM || p0.Cout % 32 != 0)) return SS_ERR_UNSUPPORTED;      // the whole channel range must sit in one tile
     ConvParams p = p0;
     p.tiles_m = (p.Cout + BM - 1) / BM;
     fast_div_setup((unsigned)p.tiles_m, &p.tm_mul, &p.tm_sh);
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
-    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, SPEC>;
+    auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, SPEC, FUSE>;
     if (smem_res > 64 * 1024) {
         // Raises this kernel's dynamic-LDS limit, once per device (the attribute belongs to the device's copy of the
         // kernel).  Two threads racing here both set it: harmless.
@@ -1036,7 +1154,7 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     TileDims t = tile_dims(desc);
     size_t wbytes = SPARSE ? packed_size(t) : dense_size(t);
     if (wbytes >= (1ull << 31)) return SS_ERR_UNSUPPORTED;
-    ConvParams p;
+    ConvParams p{};
     p.x = static_cast<const uint16_t *>(x);
     p.a_vals = static_cast<const uint8_t *>(wbuf) + kHeaderBytes;
     p.a_meta = reinterpret_cast<const uint32_t *>(p.a_vals + (size_t)t.Mt * t.Ks * 1024);
@@ -1060,6 +1178,106 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (q8) return desc->dtype == SS_I8 ? pick_mode<SS_I8, SPARSE>(desc, p, s) : pick_mode<SS_F8, SPARSE>(desc, p, s);
     return desc->dtype == SS_F16 ? pick_mode<SS_F16, SPARSE>(desc, p, s) : pick_mode<SS_BF16, SPARSE>(desc, p, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// 3x3 (or any k x k with a fast staging mode) convolution followed by a 1x1 convolution, fused
+// ---------------------------------------------------------------------------------------------
+template <int DT, bool SPARSE, int MODE, int KH, int KW>
+static int launch_fused_tile(int id, const ConvParams &p, hipStream_t s)
+{
+    switch (id) {
+        case 0: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, false, false, true>(p, s);
+        case 1: return launch<DT, SPARSE, 2, 2, 1, 1, MODE, KH, KW, true, false, true>(p, s);
+        case 2: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, false, false, true>(p, s);
+        case 3: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, false, true>(p, s);
+        case 4: return launch<DT, SPARSE, 4, 1, 1, 2, MODE, KH, KW, true, true, true>(p, s);
+        case 5: return launch<DT, SPARSE, 4, 1, 2, 2, MODE, KH, KW, true, true, true>(p, s);
+        default: break;
+    }
+    return SS_ERR_INVALID_ARG;
+}
+
+// The tile must hold every output channel of the first convolution: 64, 128 or 256 rows; among the tiles of that
+// height the grid size decides as in choose_tile.
+static int choose_fused_tile(const ConvParams &p)
+{
+    const char *env = getenv("SS_TILE");
+    if (env) return atoi(env);
+    if (p.Cout <= 64) return n_blocks(p, 64, 64) <= 1024 ? 1 : 0;
+    if (p.Cout <= 128) return n_blocks(p, 128, 64) <= 256 ? 4 : 2;
+    return n_blocks(p, 256, 64) <= 256 ? 5 : 3;
+}
+
+template <int DT, bool SPARSE>
+static int fused_mode(const ss_weight_desc *d1, const ConvParams &p, hipStream_t s)
+{
+    const int id = choose_fused_tile(p);
+    if (d1->korder == SS_K_CRS && d1->kh == 3 && d1->kw == 3 && d1->cin % 32 == 0)
+        return launch_fused_tile<DT, SPARSE, MODE_TAPS, 3, 3>(id, p, s);
+    if (d1->korder == SS_K_RSC && d1->cin % 8 == 0) return launch_fused_tile<DT, SPARSE, MODE_VEC, 1, 1>(id, p, s);
+    return SS_ERR_UNSUPPORTED;
+}
+
+template <bool SPARSE>
+static int fused_entry(const ss_weight_desc *d1, const void *x, int32_t N, int32_t H, int32_t Wd, const void *w1,
+                       const float *bias1, int32_t sh, int32_t sw, int32_t ph, int32_t pw, int32_t act1,
+                       const ss_weight_desc *d2, const void *w2, const float *bias2, const void *residual, int32_t act2,
+                       void *y, void *stream)
+{
+    int st = check_desc(d1, SPARSE);
+    if (st != SS_OK) return st;
+    st = check_desc(d2, SPARSE);
+    if (st != SS_OK) return st;
+    if (is_byte_type(d1->dtype) || d2->dtype != d1->dtype) return SS_ERR_UNSUPPORTED;
+    if (d2->kh != 1 || d2->kw != 1 || d2->cin != d1->cout) return SS_ERR_INVALID_ARG;
+    if (d1->cout % 32 != 0 || d1->cout > 256 || d2->cout % 32 != 0 || d1->kh * d1->kw == 1) return SS_ERR_UNSUPPORTED;
+    if (!x || !w1 || !w2 || !y) return SS_ERR_INVALID_ARG;
+    if (N <= 0 || H <= 0 || Wd <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return SS_ERR_INVALID_ARG;
+    for (int a : {act1, act2})
+        if (a != SS_ACT_NONE && a != SS_ACT_RELU && a != SS_ACT_GELU) return SS_ERR_INVALID_ARG;
+    if (H + 2 * ph < d1->kh || Wd + 2 * pw < d1->kw) return SS_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(w1, 16) || !aligned(w2, 16) || !aligned(y, 16) || (bias1 && !aligned(bias1, 4)) ||
+        (bias2 && !aligned(bias2, 16)) || (residual && !aligned(residual, 16)))
+        return SS_ERR_INVALID_ARG;
+    const int Ho = (H + 2 * ph - d1->kh) / sh + 1, Wo = (Wd + 2 * pw - d1->kw) / sw + 1;
+    if (Ho <= 0 || Wo <= 0) return SS_ERR_INVALID_ARG;
+    const long long P = (long long)N * Ho * Wo, xbytes = (long long)N * H * Wd * d1->cin * 2;
+    if (xbytes >= (1ll << 31) - (1ll << 26) || P * d2->cout >= (1ll << 31) || P >= (1ll << 31) - 512) return SS_ERR_UNSUPPORTED;
+    if ((long long)(ph + d1->kh + 1) * (Wd + pw + d1->kw) * d1->cin * 2 >= (1ll << 26)) return SS_ERR_UNSUPPORTED;
+    const TileDims t1 = tile_dims(d1), t2 = tile_dims(d2);
+    if ((SPARSE ? packed_size(t1) : dense_size(t1)) >= (1ull << 31) || (SPARSE ? packed_size(t2) : dense_size(t2)) >= (1ull << 31))
+        return SS_ERR_UNSUPPORTED;
+    ConvParams p{};
+    p.x = static_cast<const uint16_t *>(x);
+    p.a_vals = static_cast<const uint8_t *>(w1) + kHeaderBytes;
+    p.a_meta = reinterpret_cast<const uint32_t *>(p.a_vals + (size_t)t1.Mt * t1.Ks * 1024);
+    p.bias = bias1;
+    p.scale = nullptr;
+    p.residual = nullptr;
+    p.y = nullptr;
+    p.N = N; p.H = H; p.W = Wd; p.Cin = d1->cin; p.Cout = d1->cout; p.kh = d1->kh; p.kw = d1->kw;
+    p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.Ho = Ho; p.Wo = Wo; p.P = (int)P;
+    p.K = t1.K; p.Ks = t1.Ks; p.Kp = t1.Kp; p.Mt = t1.Mt; p.act = act1; p.korder = d1->korder;
+    p.tiles_m = 0;
+    p.tm_mul = p.tm_sh = 0;
+    fast_div_setup((unsigned)(Ho * Wo), &p.howo_mul, &p.howo_sh);
+    fast_div_setup((unsigned)Wo, &p.wo_mul, &p.wo_sh);
+    fast_div_setup((unsigned)p.Cin, &p.cin_mul, &p.cin_sh);
+    fast_div_setup((unsigned)p.kw, &p.kw_mul, &p.kw_sh);
+    p.x_bytes = (unsigned)xbytes;
+    p.a_bytes = (unsigned)((size_t)t1.Mt * t1.Ks * (SPARSE ? 1024 : 2048));
+    p.meta_bytes = SPARSE ? (unsigned)((size_t)t1.Mt * t1.Kp * 256) : 4u;
+    p.a2_vals = static_cast<const uint8_t *>(w2) + kHeaderBytes;
+    p.a2_meta = reinterpret_cast<const uint32_t *>(p.a2_vals + (size_t)t2.Mt * t2.Ks * 1024);
+    p.bias2 = bias2;
+    p.res2 = static_cast<const uint16_t *>(residual);
+    p.y2 = static_cast<uint16_t *>(y);
+    p.Cout2 = d2->cout; p.Ks2 = t2.Ks; p.Kp2 = t2.Kp; p.Mt2 = t2.Mt; p.act2 = act2;
+    p.a2_bytes = (unsigned)((size_t)t2.Mt * t2.Ks * (SPARSE ? 1024 : 2048));
+    p.meta2_bytes = SPARSE ? (unsigned)((size_t)t2.Mt * t2.Kp * 256) : 4u;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return d1->dtype == SS_F16 ? fused_mode<SS_F16, SPARSE>(d1, p, s) : fused_mode<SS_BF16, SPARSE>(d1, p, s);
 }
 
 }  // namespace ss
@@ -1130,4 +1348,24 @@ extern "C" int ss_conv2d_q8_dense_fwd(const ss_weight_desc *desc, const void *x,
     if (out_dtype != SS_F16) return out_dtype == SS_BF16 ? SS_ERR_UNSUPPORTED : SS_ERR_INVALID_ARG;
     return conv_entry<false>(desc, x, N, H, Wd, dense, bias, nullptr, stride_h, stride_w, pad_h, pad_w, act, y,
                              workspace, ws_bytes, stream, true, scale);
+}
+
+extern "C" int ss_conv2d_pw_fused_fwd(const ss_weight_desc *desc1, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                      const void *packed1, const float *bias1, int32_t stride_h, int32_t stride_w,
+                                      int32_t pad_h, int32_t pad_w, int32_t act1, const ss_weight_desc *desc2,
+                                      const void *packed2, const float *bias2, const void *residual, int32_t act2,
+                                      void *y, void *stream)
+{
+    return fused_entry<true>(desc1, x, N, H, Wd, packed1, bias1, stride_h, stride_w, pad_h, pad_w, act1, desc2, packed2,
+                             bias2, residual, act2, y, stream);
+}
+
+extern "C" int ss_conv2d_pw_fused_dense_fwd(const ss_weight_desc *desc1, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                            const void *dense1, const float *bias1, int32_t stride_h, int32_t stride_w,
+                                            int32_t pad_h, int32_t pad_w, int32_t act1, const ss_weight_desc *desc2,
+                                            const void *dense2, const float *bias2, const void *residual, int32_t act2,
+                                            void *y, void *stream)
+{
+    return fused_entry<false>(desc1, x, N, H, Wd, dense1, bias1, stride_h, stride_w, pad_h, pad_w, act1, desc2, dense2,
+                              bias2, residual, act2, y, stream);
 }

@@ -1,0 +1,154 @@
+"""GPU parity of the fused k x k -> 1x1 pair (ss_conv2d_pw_fused_fwd and its dense twin) against the oracle, which
+evaluates the two layers one after the other with the intermediate rounded to the 16-bit type in between."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2411_00288_amd import workloads as wl
+from helpers import check_close, dev_bits, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(N, H, W, cin, cmid, cout, k=3, s=1, p=1, dtype=wl.BF16, korder=wl.K_CRS, act1=wl.ACT_RELU, act2=wl.ACT_RELU, seed=0):
+    L1 = wl.Layer(f"f{N}x{H}x{W}c{cin}m{cmid}o{cout}k{k}s{s}d{dtype}o{korder}", N=N, H=H, W=W, cin=cin, cout=cmid, kh=k, kw=k,
+                  stride=s, pad=p, dtype=dtype, korder=korder, act=act1, mask="logits", seed=seed)
+    L2 = wl.Layer("second", N=N, H=L1.Ho, W=L1.Wo, cin=cmid, cout=cout, kh=1, kw=1, dtype=dtype, act=act2, mask="logits",
+                  seed=seed + 1000)
+    return L1, L2
+
+
+def _oracle_pair(L1, L2, d1, d2, res_bits):
+    t = oracle.conv2d(d1["x"], d1["W"], d1["M"], cin=L1.cin, kh=L1.kh, kw=L1.kw, korder=L1.korder, dtype=L1.dtype,
+                      bias=d1["bias"], stride=(L1.stride,) * 2, pad=(L1.pad,) * 2, act=L1.act)
+    t_bits = wl.to_bits(t.astype(np.float32), L1.dtype)
+    y = oracle.conv2d(t_bits, d2["W"], d2["M"], cin=L2.cin, kh=1, kw=1, korder=L2.korder, dtype=L2.dtype, bias=d2["bias"],
+                      act=L2.act, residual=res_bits)
+    return t_bits, y
+
+
+def _run(ss, L1, L2, d1, d2, res_bits, sparse):
+    dsc1 = ss.make_desc(L1.cout, L1.cin, L1.kh, L1.kw, L1.dtype, L1.korder)
+    dsc2 = ss.make_desc(L2.cout, L2.cin, 1, 1, L2.dtype, L2.korder)
+    x = dev_bits(d1["x"], L1.dtype)
+    W1, M1 = dev_bits(d1["W"], L1.dtype), torch.from_numpy(d1["M"]).cuda()
+    W2, M2 = dev_bits(d2["W"], L2.dtype), torch.from_numpy(d2["M"]).cuda()
+    b1, b2 = torch.from_numpy(d1["bias"]).cuda(), torch.from_numpy(d2["bias"]).cuda()
+    res = None if res_bits is None else dev_bits(res_bits, L1.dtype)
+    st, pd = (L1.stride,) * 2, (L1.pad,) * 2
+    if sparse:
+        y = ss.ss_conv2d_pw_fused_fwd(dsc1, x, ss.ss_mask_compress(dsc1, W1, M1), b1, st, pd, L1.act, dsc2,
+                                      ss.ss_mask_compress(dsc2, W2, M2), b2, res, L2.act)
+        # the two separate calls on the same operands
+        t = ss.ss_conv2d_fwd(dsc1, x, ss.ss_mask_compress(dsc1, W1, M1), b1, st, pd, L1.act)
+        y_sep = ss.ss_conv2d_res_fwd(dsc2, t, ss.ss_mask_compress(dsc2, W2, M2), b2, res, (1, 1), (0, 0), L2.act)
+    else:
+        y = ss.ss_conv2d_pw_fused_dense_fwd(dsc1, x, ss.ss_dense_pack(dsc1, W1, M1), b1, st, pd, L1.act, dsc2,
+                                            ss.ss_dense_pack(dsc2, W2, M2), b2, res, L2.act)
+        t = ss.ss_conv2d_dense_fwd(dsc1, x, ss.ss_dense_pack(dsc1, W1, M1), b1, st, pd, L1.act)
+        y_sep = ss.ss_conv2d_dense_res_fwd(dsc2, t, ss.ss_dense_pack(dsc2, W2, M2), b2, res, (1, 1), (0, 0), L2.act)
+    torch.cuda.synchronize()
+    return y, y_sep
+
+
+PAIRS = [
+    _pair(2, 14, 14, 64, 64, 256),                                   # stage-1 bottleneck shape (small image): 64-row tile
+    _pair(3, 9, 11, 64, 128, 512, seed=2),                           # 128-row tile, ragged pixels
+    _pair(2, 7, 9, 96, 256, 1024, dtype=wl.F16, seed=3),             # 256-row tile
+    _pair(2, 15, 13, 32, 96, 160, s=2, seed=4),                      # stride 2, cout1 = 96 inside a 128-row tile, 5 row tiles of the second layer
+    _pair(2, 10, 10, 24, 64, 96, korder=wl.K_RSC, seed=5),           # channels-last flattening of the first layer
+    _pair(1, 12, 12, 40, 128, 64, k=5, p=2, korder=wl.K_RSC, act1=wl.ACT_NONE, act2=wl.ACT_GELU, dtype=wl.F16, seed=6),
+]
+
+
+@pytest.fixture
+def force_tile():
+    old = os.environ.get("SS_TILE")
+
+    def setter(tid):
+        if tid is None:
+            os.environ.pop("SS_TILE", None)
+        else:
+            os.environ["SS_TILE"] = str(tid)
+    yield setter
+    if old is None:
+        os.environ.pop("SS_TILE", None)
+    else:
+        os.environ["SS_TILE"] = old
+
+
+def _tiles_for(cmid):
+    return [None] + ([0, 1] if cmid <= 64 else []) + ([2, 4] if cmid <= 128 else []) + [3, 5]
+
+
+@pytest.mark.parametrize("with_res", [True, False])
+@pytest.mark.parametrize("pair", PAIRS, ids=lambda pr: pr[0].name)
+def test_fused_pair_matches_oracle_chain(ss, force_tile, pair, with_res):
+    L1, L2 = pair
+    d1, d2 = wl.make_inputs(L1), wl.make_inputs(L2)
+    res_bits = None
+    if with_res:
+        rng = np.random.Generator(np.random.PCG64(5 + L1.seed))
+        res_bits = wl.to_bits(rng.standard_normal((L1.N, L1.Ho, L1.Wo, L2.cout), dtype=np.float32), L1.dtype)
+    t_bits, ref = _oracle_pair(L1, L2, d1, d2, res_bits)
+    for tile in _tiles_for(L1.cout):
+        force_tile(tile)
+        for sparse in (True, False):
+            y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
+            what = f"{L1.name} tile {tile} {'sparse' if sparse else 'dense'} res {with_res}"
+            # The intermediate's rounding can differ in the last bit between the GPU's fp32 and the oracle's fp64 sums,
+            # and such a difference then passes through the second layer: the bound is that of two layers.
+            got = y.float().cpu().numpy().astype(np.float64)
+            assert np.isfinite(got).all(), what
+            rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+            assert rel <= 4e-3, f"{what}: rel-L2 {rel:.3e}"
+            assert (np.abs(got - ref) <= 2e-2 * (np.abs(ref) + 1)).all(), what
+            # against the library's own two separate calls the difference is one rounding of the output at most
+            sep = y_sep.float().cpu().numpy().astype(np.float64)
+            assert (np.abs(got - sep) <= 2.0 ** -7 * (np.abs(sep) + 1e-3)).all(), what
+
+
+@pytest.mark.parametrize("cmid", [64, 128, 256])
+def test_fused_pair_is_bit_exact_on_integers(ss, force_tile, cmid):
+    L1, L2 = _pair(2, 9, 8, 32, cmid, 96, act1=wl.ACT_RELU, act2=wl.ACT_NONE, dtype=wl.F16, seed=11)
+    d1, d2 = wl.make_small_int_inputs(L1, seed=1), wl.make_small_int_inputs(L2, seed=2)
+    # keep every value an exactly representable integer: |t| <= 2*K1/2 + 2 <= 290, second sums <= 290 * cmid / 2
+    d2["W"] = wl.to_bits((wl.from_bits(d2["W"], wl.F16) * (np.arange(cmid) % 8 == 0)).astype(np.float32), wl.F16)
+    res_bits = wl.to_bits(np.random.default_rng(3).integers(-3, 4, size=(L1.N, L1.Ho, L1.Wo, L2.cout)).astype(np.float32), wl.F16)
+    t_bits, ref = _oracle_pair(L1, L2, d1, d2, res_bits)
+    assert np.abs(ref).max() <= 2048 and np.abs(oracle.bits_to_double(t_bits, wl.F16)).max() <= 2048
+    for tile in _tiles_for(cmid):
+        force_tile(tile)
+        for sparse in (True, False):
+            y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
+            assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref), (tile, sparse)
+            assert np.array_equal(host_bits(y), host_bits(y_sep))
+
+
+def test_fused_argument_errors(ss):
+    L1, L2 = _pair(1, 8, 8, 32, 64, 128)
+    d1, d2 = wl.make_inputs(L1), wl.make_inputs(L2)
+    x = dev_bits(d1["x"], L1.dtype)
+    dsc1 = ss.make_desc(64, 32, 3, 3, L1.dtype, wl.K_CRS)
+    dsc2 = ss.make_desc(128, 64, 1, 1, L1.dtype, wl.K_CRS)
+    p1 = ss.ss_mask_compress(dsc1, dev_bits(d1["W"], L1.dtype), torch.from_numpy(d1["M"]).cuda())
+    p2 = ss.ss_mask_compress(dsc2, dev_bits(d2["W"], L2.dtype), torch.from_numpy(d2["M"]).cuda())
+
+    def status(fn):
+        with pytest.raises(ss.SSError) as e:
+            fn()
+        return e.value.status
+
+    bad2 = ss.make_desc(128, 32, 1, 1, L1.dtype, wl.K_CRS)           # cin of the second layer != cout of the first
+    assert status(lambda: ss.ss_conv2d_pw_fused_fwd(dsc1, x, p1, None, (1, 1), (1, 1), 0, bad2, p2)) == ss.SS_ERR_INVALID_ARG
+    k3 = ss.make_desc(128, 64, 3, 3, L1.dtype, wl.K_CRS)             # the second layer must be 1x1
+    assert status(lambda: ss.ss_conv2d_pw_fused_fwd(dsc1, x, p1, None, (1, 1), (1, 1), 0, k3, p2)) == ss.SS_ERR_INVALID_ARG
+    wide = ss.make_desc(512, 32, 3, 3, L1.dtype, wl.K_CRS)           # more output channels than a tile holds
+    pw = torch.zeros(ss.ss_packed_bytes(wide), dtype=torch.uint8, device="cuda")
+    d512 = ss.make_desc(128, 512, 1, 1, L1.dtype, wl.K_CRS)
+    p512 = torch.zeros(ss.ss_packed_bytes(d512), dtype=torch.uint8, device="cuda")
+    assert status(lambda: ss.ss_conv2d_pw_fused_fwd(wide, x, pw, None, (1, 1), (1, 1), 0, d512, p512)) == ss.SS_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
