@@ -319,12 +319,52 @@ def print_tail_table(torch, ss, wl, steps, warmup):
         torch.cuda.empty_cache()
 
 
+def print_fused_table(torch, ss, wl, steps, warmup, batch=64):
+    """The 3x3 -> 1x1 (+ residual, ReLU) pairs of the ResNet-50 bottlenecks: one fused kernel against the two separate
+    calls (the second with its fused tail), sparse path and dense twin."""
+    import dataclasses
+    layers = {L.name: L for L in wl.resnet50_layers(batch)}
+    pairs = [("s1_c2_3x3_64_64", "s1_c3_1x1_64_256"), ("s2_c2_3x3_128_128", "s2_c3_1x1_128_512"),
+             ("s2_c2_3x3_128_128_s2", "s2_c3_1x1_128_512"), ("s3_c2_3x3_256_256", "s3_c3_1x1_256_1024"),
+             ("s3_c2_3x3_256_256_s2", "s3_c3_1x1_256_1024")]
+    print(f"{'pair':44s} {'fused us':>9s} {'separate us':>12s} {'gain':>6s} {'twin fused':>11s} {'twin separate':>14s}")
+    for n1, n2 in pairs:
+        L1, L2 = layers[n1], dataclasses.replace(layers[n2], act=wl.ACT_RELU)
+        tdt = ss.torch_dtype(L1.dtype)
+        g = torch.Generator(device="cuda").manual_seed(1)
+        pat = torch.tensor([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]], dtype=torch.uint8, device="cuda")
+
+        def weights(L):
+            W = (torch.randn((L.cout, L.K), generator=g, device="cuda") * (2.0 / L.K) ** 0.5).to(tdt)
+            M = pat[torch.randint(0, 6, (L.cout, L.K // 4), generator=g, device="cuda")].reshape(L.cout, L.K).contiguous()
+            d = ss.make_desc(L.cout, L.cin, L.kh, L.kw, L.dtype, L.korder)
+            return d, ss.ss_mask_compress(d, W, M), ss.ss_dense_pack(d, W, M), torch.randn(L.cout, generator=g, device="cuda") * 0.1
+        d1, p1, q1, b1 = weights(L1)
+        d2, p2, q2, b2 = weights(L2)
+        x = torch.randn((L1.N, L1.H, L1.W, L1.cin), generator=g, device="cuda").clamp_(min=0).to(tdt)
+        res = torch.randn((L1.N, L1.Ho, L1.Wo, L2.cout), generator=g, device="cuda").to(tdt)
+        st, pd = (L1.stride,) * 2, (L1.pad,) * 2
+        out = {}
+        for sparse, w1, w2 in ((True, p1, p2), (False, q1, q2)):
+            fused, _ = ss.prepare_conv2d_pw_fused(d1, x, w1, b1, st, pd, wl.ACT_RELU, d2, w2, b2, res, wl.ACT_RELU, sparse=sparse)
+            c1, t = ss.prepare_conv2d(d1, x, w1, b1, st, pd, wl.ACT_RELU, sparse=sparse)
+            c2, _ = ss.prepare_conv2d(d2, t, w2, b2, (1, 1), (0, 0), wl.ACT_RELU, sparse=sparse, residual=res)
+
+            def separate():
+                c1()
+                c2()
+            out[sparse] = (median_time(torch, fused, steps, warmup, reps=3) * 1e3, median_time(torch, separate, steps, warmup, reps=3) * 1e3)
+        print(f"{n1 + ' -> ' + n2:44s} {out[True][0]:9.1f} {out[True][1]:12.1f} {out[True][1] / out[True][0]:6.2f} "
+              f"{out[False][0]:11.1f} {out[False][1]:14.1f}", flush=True)
+
+
 def print_trunk(torch, ss, wl, batch=64, image=224):
     """End-to-end ResNet-50 convolution trunk (53 convolutions + max pool, real dataflow, fused residual tails),
     replayed as one HIP graph: images per second on the sparse path and on the dense twin."""
     from paper_2411_00288_amd import resnet50
     print(f"## ResNet-50 convolution trunk, batch {batch}, {image}x{image} (+ a zero fourth channel), bf16, synthetic weights: stem (dense) -> max pool -> "
-          "16 bottlenecks; 48 convolutions 2:4-masked, stem and 4 shortcut convolutions dense; add + ReLU fused into conv3")
+          "16 bottlenecks; 48 convolutions 2:4-masked, stem and 4 shortcut convolutions dense; add + ReLU fused into conv3; "
+          "3x3 + conv3 of the first two stages in one kernel")
     for sparse in (True, False):
         t = resnet50.Trunk(batch=batch, image=image, dtype=wl.BF16, sparse=sparse)
         t.input.copy_(torch.randn(t.input.shape, device="cuda").to(torch.bfloat16))
@@ -347,6 +387,7 @@ def main():
     ap.add_argument("--only", default="", help="with --table: only layers whose name contains this string")
     ap.add_argument("--trunk", action="store_true", help="end-to-end ResNet-50 convolution trunk (images/s) instead of the JSON line")
     ap.add_argument("--q8", action="store_true", help="report of the 8-bit integer precision point instead of the JSON line")
+    ap.add_argument("--fused", action="store_true", help="report of the fused 3x3 -> 1x1 bottleneck pairs instead of the JSON line")
     ap.add_argument("--tail", action="store_true", help="report of the fused residual / activation tail instead of the JSON line")
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
@@ -370,6 +411,9 @@ def main():
 
     if args.trunk:
         print_trunk(torch, ss, wl)
+        return
+    if args.fused:
+        print_fused_table(torch, ss, wl, min(args.steps, 100), min(args.warmup, 20))
         return
     if args.q8:
         print_q8_table(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50))

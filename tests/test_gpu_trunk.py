@@ -21,7 +21,8 @@ def _conv_ref(L, d, x_bits, res_bits):
 @pytest.mark.parametrize("sparse,channels", [(True, 4), (False, 4), (True, 3)])
 def test_trunk_ops_match_oracle_on_their_actual_inputs(ss, sparse, channels):
     from paper_2411_00288_amd import resnet50
-    t = resnet50.Trunk(batch=1, image=64, dtype=wl.BF16, sparse=sparse, keep_host=True, image_channels=channels)
+    t = resnet50.Trunk(batch=1, image=64, dtype=wl.BF16, sparse=sparse, keep_host=True, image_channels=channels,
+                       fuse_pairs=False)                        # every layer writes its own buffer
     assert sum(op.kind == "conv" for op in t.ops) == 53 and t.output.shape == (1, 2, 2, 2048)
     rng = np.random.Generator(np.random.PCG64(77))
     x = rng.standard_normal((1, 64, 64, channels), dtype=np.float32)
@@ -79,3 +80,25 @@ def test_maxpool_matches_oracle_bit_for_bit(ss):
         assert np.array_equal(host_bits(y), oracle.maxpool2d(xb, dtype=dtype, k=k, stride=s, pad=p))
     with pytest.raises(ss.SSError):
         ss.ss_maxpool2d(torch.zeros((1, 4, 4, 12), dtype=torch.float16, device="cuda"))       # C % 8 != 0
+
+
+@pytest.mark.parametrize("sparse", [True, False])
+def test_trunk_with_fused_pairs_equals_the_unfused_trunk(ss, sparse):
+    """Running a block's 3x3 and 1x1 expansion as one kernel changes only the order of fp32 additions in the 1x1."""
+    from paper_2411_00288_amd import resnet50
+    a = resnet50.Trunk(batch=2, image=64, dtype=wl.BF16, sparse=sparse, fuse_pairs=False)
+    b = resnet50.Trunk(batch=2, image=64, dtype=wl.BF16, sparse=sparse, fuse_pairs=True)
+    assert len(b.fused) == (7 if sparse else 3) and len(b.launches) == len(a.launches) - len(b.fused)
+    x = torch.randn(a.input.shape, device="cuda").to(torch.bfloat16)
+    x[..., 3:] = 0
+    a.input.copy_(x)
+    b.input.copy_(x)
+    a.forward()
+    b.forward()
+    torch.cuda.synchronize()
+    ya, yb = a.output.float(), b.output.float()
+    assert torch.isfinite(yb).all()
+    assert (torch.linalg.norm(ya - yb) / torch.linalg.norm(ya)).item() <= 1e-2
+    # the buffers of the stages that do not fuse anything upstream are identical
+    first_c1 = next(op for op in a.ops if op.name == "s1b0_c1")
+    assert torch.equal(a.bufs[first_c1.dst], b.bufs[first_c1.dst])
