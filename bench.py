@@ -324,12 +324,17 @@ def print_fused_table(torch, ss, wl, steps, warmup, batch=64):
     calls (the second with its fused tail), sparse path and dense twin."""
     import dataclasses
     layers = {L.name: L for L in wl.resnet50_layers(batch)}
-    pairs = [("s1_c2_3x3_64_64", "s1_c3_1x1_64_256"), ("s2_c2_3x3_128_128", "s2_c3_1x1_128_512"),
-             ("s2_c2_3x3_128_128_s2", "s2_c3_1x1_128_512"), ("s3_c2_3x3_256_256", "s3_c3_1x1_256_1024"),
-             ("s3_c2_3x3_256_256_s2", "s3_c3_1x1_256_1024")]
+    layers.update({L.name: L for L in wl.convnext_t_stage1_layers()})
+    # (first layer, second layer, activation after the first, activation after the second + residual)
+    pairs = [("s1_c2_3x3_64_64", "s1_c3_1x1_64_256", wl.ACT_RELU, wl.ACT_RELU),
+             ("s2_c2_3x3_128_128", "s2_c3_1x1_128_512", wl.ACT_RELU, wl.ACT_RELU),
+             ("s2_c2_3x3_128_128_s2", "s2_c3_1x1_128_512", wl.ACT_RELU, wl.ACT_RELU),
+             ("s3_c2_3x3_256_256", "s3_c3_1x1_256_1024", wl.ACT_RELU, wl.ACT_RELU),
+             ("s3_c2_3x3_256_256_s2", "s3_c3_1x1_256_1024", wl.ACT_RELU, wl.ACT_RELU),
+             ("cnx_pw_96_384", "cnx_pw_384_96", wl.ACT_GELU, wl.ACT_NONE)]      # the ConvNeXt block's inverted bottleneck, batch 128
     print(f"{'pair':44s} {'fused us':>9s} {'separate us':>12s} {'gain':>6s} {'twin fused':>11s} {'twin separate':>14s}")
-    for n1, n2 in pairs:
-        L1, L2 = layers[n1], dataclasses.replace(layers[n2], act=wl.ACT_RELU)
+    for n1, n2, act1, act2 in pairs:
+        L1, L2 = layers[n1], layers[n2]
         tdt = ss.torch_dtype(L1.dtype)
         g = torch.Generator(device="cuda").manual_seed(1)
         pat = torch.tensor([[1, 1, 0, 0], [1, 0, 1, 0], [1, 0, 0, 1], [0, 1, 1, 0], [0, 1, 0, 1], [0, 0, 1, 1]], dtype=torch.uint8, device="cuda")
@@ -346,9 +351,9 @@ def print_fused_table(torch, ss, wl, steps, warmup, batch=64):
         st, pd = (L1.stride,) * 2, (L1.pad,) * 2
         out = {}
         for sparse, w1, w2 in ((True, p1, p2), (False, q1, q2)):
-            fused, _ = ss.prepare_conv2d_pw_fused(d1, x, w1, b1, st, pd, wl.ACT_RELU, d2, w2, b2, res, wl.ACT_RELU, sparse=sparse)
-            c1, t = ss.prepare_conv2d(d1, x, w1, b1, st, pd, wl.ACT_RELU, sparse=sparse)
-            c2, _ = ss.prepare_conv2d(d2, t, w2, b2, (1, 1), (0, 0), wl.ACT_RELU, sparse=sparse, residual=res)
+            fused, _ = ss.prepare_conv2d_pw_fused(d1, x, w1, b1, st, pd, act1, d2, w2, b2, res, act2, sparse=sparse)
+            c1, t = ss.prepare_conv2d(d1, x, w1, b1, st, pd, act1, sparse=sparse)
+            c2, _ = ss.prepare_conv2d(d2, t, w2, b2, (1, 1), (0, 0), act2, sparse=sparse, residual=res)
 
             def separate():
                 c1()

@@ -219,14 +219,18 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
                             void *y, void *workspace, size_t ws_bytes, void *stream);
 
 /*
- * Two masked convolutions in one kernel: a k x k convolution (k > 1) whose every output channel fits one tile,
- * followed by a 1x1 convolution on its output -- the 3x3 -> 1x1 expansion that closes a ResNet bottleneck:
+ * Two masked convolutions in one kernel: a convolution whose output tile can be held on chip, followed by a 1x1
+ * convolution on its output -- the 3x3 -> 1x1 expansion that closes a ResNet bottleneck, or the two pointwise
+ * layers of a ConvNeXt block:
  *     t = act1( conv_kxk(x; W1) + bias1 )          rounded to the 16-bit type, exactly as ss_conv2d_fwd would store it
  *     y = act2( conv_1x1(t; W2) + bias2 + residual ) = what ss_conv2d_res_fwd would compute from t
  * The intermediate t never leaves the compute unit's LDS, which saves its write and read (the results are those
  * of the two separate calls up to the order of the fp32 additions in the second one).
- *   desc1   the k x k layer: 16-bit dtype, cout % 32 == 0, cout <= 256, and either SS_K_CRS with a 3x3 kernel and
- *           cin % 32 == 0, or SS_K_RSC with cin % 8 == 0 -- otherwise SS_ERR_UNSUPPORTED
+ *   desc1   the first layer, 16-bit dtype.  Either k x k with k > 1: cout % 32 == 0, cout <= 256, and SS_K_CRS with a
+ *           3x3 kernel and cin % 32 == 0, or SS_K_RSC with cin % 8 == 0.  Or 1x1 (the inverted bottleneck of a
+ *           ConvNeXt block, narrow -> wide -> narrow: the wide intermediate is produced and consumed 128 channels
+ *           at a time): stride 1, no padding, cin % 32 == 0, cin <= 128, cout % 128 == 0 (any width), bias1 16-byte
+ *           aligned, and desc2->cout <= 128.  Anything else: SS_ERR_UNSUPPORTED
  *   desc2   the 1x1 layer: same dtype, cin == desc1->cout, cout % 32 == 0
  *   packed1, packed2   written by ss_mask_compress for desc1 / desc2                         (read only)
  *   bias1   [desc1->cout] fp32 or NULL; bias2 [desc2->cout] fp32, 16-byte aligned, or NULL     (read only)

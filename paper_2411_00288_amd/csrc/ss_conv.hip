@@ -960,6 +960,244 @@ void conv_kernel(ConvParams p)
 }
 
 // ---------------------------------------------------------------------------------------------
+// 1x1 -> activation -> 1x1 (+ residual): the inverted bottleneck of a ConvNeXt block (narrow -> 4x wide -> narrow)
+// in one kernel.  A workgroup owns 64 pixels.  Their input rows are staged in LDS once; the wide intermediate is
+// produced 128 channels at a time (first contraction, bias, activation, rounding to 16 bit, LDS) and consumed at
+// once by the second contraction, whose accumulators stay in registers across the chunks.  The intermediate, four
+// times the size of the block's input and output, never reaches memory.
+// ---------------------------------------------------------------------------------------------
+struct MlpParams {
+    const uint16_t *x;        // [P][Cin]
+    const uint8_t *a1_vals, *a2_vals;
+    const uint32_t *a1_meta, *a2_meta;
+    const float *bias1, *bias2;
+    const uint16_t *res2;     // [P][Cout2] or nullptr
+    uint16_t *y2;             // [P][Cout2]
+    int P, Cin, Cmid, Cout2, Ks1, Kp1, Ks2, Kp2, Mt2, act1, act2;
+    unsigned a1_bytes, meta1_bytes, a2_bytes, meta2_bytes;
+};
+
+constexpr int kMlpKs1 = 4;        // first reduction: at most 128 input channels
+constexpr int kMlpTiles = 2;      // 32x32 output tiles of the second layer per wave: at most 128 output channels x 64 pixels over 4 waves
+
+template <int DT, bool SPARSE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void mlp_kernel(MlpParams p)
+{
+    constexpr int BN = 64, CH = 128;                      // pixels per workgroup, intermediate channels per chunk
+    constexpr int CROW = CH + 4;                          // halfs per pixel row of the intermediate chunk (8-byte aligned rows)
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    const int XROW = p.Cin + 8;                           // halfs per pixel row of the input tile (16-byte aligned rows)
+    uint16_t *Xs = smem;
+    uint16_t *Cs = smem + BN * XROW;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, c = lane & 31;
+    const int n0 = blockIdx.x * BN;
+    const __amdgpu_buffer_rsrc_t r1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a1_vals), 0, (int)p.a1_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t m1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a1_meta), 0, (int)p.meta1_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t r2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a2_vals), 0, (int)p.a2_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t m2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a2_meta), 0, (int)p.meta2_bytes, kRsrcFlags);
+
+    struct Row1 {                                         // one 32-row tile of the first layer: all its reduction steps, and its bias
+        u32x4 v[SPARSE ? 1 : 2][kMlpKs1];
+        uint32_t idx[kMlpKs1];
+        float4 b[4];
+    };
+    auto load_row1 = [&](Row1 &r, int mt) {
+#pragma unroll
+        for (int s = 0; s < kMlpKs1; s++) {
+            if (s >= p.Ks1) break;                        // uniform
+            if constexpr (SPARSE) {
+                r.v[0][s] = __builtin_amdgcn_raw_buffer_load_b128(r1, (int)(((unsigned)(mt * p.Ks1 + s) * 64 + lane) * 16u), 0, 0);
+                r.idx[s] = __builtin_amdgcn_raw_buffer_load_b32(m1, (int)(((unsigned)(mt * p.Kp1 + (s >> 1)) * 64 + lane) * 4u), 0, 0);
+            } else {
+                const unsigned off = ((unsigned)(mt * p.Ks1 + s) * 128 + lane) * 16u;
+                r.v[0][s] = __builtin_amdgcn_raw_buffer_load_b128(r1, (int)off, 0, 0);
+                r.v[1][s] = __builtin_amdgcn_raw_buffer_load_b128(r1, (int)off, 1024, 0);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+            r.b[q] = p.bias1 ? *reinterpret_cast<const float4 *>(p.bias1 + mt * 32 + 8 * q + 4 * g) : make_float4(0.f, 0.f, 0.f, 0.f);
+    };
+    // the second layer's weights for this wave's output tiles and the 4 reduction steps of one chunk
+    struct Row2 {
+        u32x4 v[SPARSE ? 1 : 2][kMlpTiles][4];
+        uint32_t idx[kMlpTiles][4];
+    };
+    const int ntiles2 = p.Mt2 * 2;                        // output tiles of the second layer: (row tile, pixel half)
+    auto load_row2 = [&](Row2 &r, int mc) {
+#pragma unroll
+        for (int ti = 0; ti < kMlpTiles; ti++) {
+            const int t = wave + 4 * ti;
+            if (t >= ntiles2) break;                      // uniform
+            const int rt = t >> 1;
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const int ks = mc * 4 + s;
+                if constexpr (SPARSE) {
+                    r.v[0][ti][s] = __builtin_amdgcn_raw_buffer_load_b128(r2, (int)(((unsigned)(rt * p.Ks2 + ks) * 64 + lane) * 16u), 0, 0);
+                    r.idx[ti][s] = __builtin_amdgcn_raw_buffer_load_b32(m2, (int)(((unsigned)(rt * p.Kp2 + (ks >> 1)) * 64 + lane) * 4u), 0, 0);
+                } else {
+                    const unsigned off = ((unsigned)(rt * p.Ks2 + ks) * 128 + lane) * 16u;
+                    r.v[0][ti][s] = __builtin_amdgcn_raw_buffer_load_b128(r2, (int)off, 0, 0);
+                    r.v[1][ti][s] = __builtin_amdgcn_raw_buffer_load_b128(r2, (int)off, 1024, 0);
+                }
+            }
+        }
+    };
+
+    Row1 a1, a1n;
+    Row2 a2;
+    load_row1(a1, wave);
+    // ---- the input tile: 64 pixel rows of Cin channels, 16-byte vectors, zeros past the last pixel
+    {
+        const int upr = p.Cin >> 3;                       // 16-byte units per row
+        for (int i = tid; i < BN * upr; i += 256) {
+            const int px = i / upr, u = i - px * upr;
+            const int pg = n0 + px;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (pg < p.P) v = *reinterpret_cast<const u32x4 *>(p.x + (size_t)pg * p.Cin + u * 8);
+            *reinterpret_cast<u32x4 *>(Xs + px * XROW + u * 8) = v;
+        }
+    }
+    f32x16 acc2[kMlpTiles];
+#pragma unroll
+    for (int ti = 0; ti < kMlpTiles; ti++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc2[ti][v] = 0.f;
+    const float floor1 = p.act1 == SS_ACT_RELU ? 0.f : -__builtin_inff();
+    __syncthreads();
+
+    const int nchunks = p.Cmid / CH;
+    for (int mc = 0; mc < nchunks; mc++) {
+        load_row2(a2, mc);                                // in flight while the first contraction runs
+        // ---- first contraction: rows 128*mc + 32*wave + [0,32) of the intermediate, all 64 pixels
+        f32x16 acc1[2];
+#pragma unroll
+        for (int tn = 0; tn < 2; tn++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc1[tn][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < kMlpKs1; s++) {
+            if (s >= p.Ks1) break;                        // uniform
+#pragma unroll
+            for (int tn = 0; tn < 2; tn++) {
+                const uint16_t *src = Xs + (tn * 32 + c) * XROW + 32 * s + 16 * g;
+                B32 bf;
+                bf.lo = *reinterpret_cast<const u32x4 *>(src);
+                bf.hi = *reinterpret_cast<const u32x4 *>(src + 8);
+                if constexpr (SPARSE) {
+                    acc1[tn] = mma_sparse<DT>(a1.v[0][s], bf, acc1[tn], a1.idx[s] >> ((s & 1) * 16));
+                } else {
+                    acc1[tn] = mma_dense<DT>(a1.v[0][s], bf.lo, acc1[tn]);
+                    acc1[tn] = mma_dense<DT>(a1.v[1][s], bf.hi, acc1[tn]);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const float bv[4] = {a1.b[q].x, a1.b[q].y, a1.b[q].z, a1.b[q].w};
+#pragma unroll
+            for (int tn = 0; tn < 2; tn++) {
+                float r[4];
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const float z = acc1[tn][4 * q + e] + bv[e];
+                    r[e] = p.act1 == SS_ACT_GELU ? z * normal_cdf(z) : (z < floor1 ? 0.f : z);
+                }
+                *reinterpret_cast<uint2 *>(Cs + (tn * 32 + c) * CROW + wave * 32 + 8 * q + 4 * g) =
+                    make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
+            }
+        }
+        if (mc + 1 < nchunks) load_row1(a1n, (mc + 1) * 4 + wave);      // in flight while the second contraction runs
+        __syncthreads();
+        // ---- second contraction: this chunk's 128 intermediate channels into the output accumulators
+#pragma unroll
+        for (int ti = 0; ti < kMlpTiles; ti++) {
+            const int t = wave + 4 * ti;
+            if (t >= ntiles2) break;                      // uniform
+            const int ct = t & 1;
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const uint16_t *src = Cs + (ct * 32 + c) * CROW + 32 * s + 16 * g;       // 8-byte aligned
+                const uint2 u0 = *reinterpret_cast<const uint2 *>(src), u1 = *reinterpret_cast<const uint2 *>(src + 4);
+                const uint2 u2 = *reinterpret_cast<const uint2 *>(src + 8), u3 = *reinterpret_cast<const uint2 *>(src + 12);
+                B32 bf;
+                bf.lo = u32x4{u0.x, u0.y, u1.x, u1.y};
+                bf.hi = u32x4{u2.x, u2.y, u3.x, u3.y};
+                if constexpr (SPARSE) {
+                    acc2[ti] = mma_sparse<DT>(a2.v[0][ti][s], bf, acc2[ti], a2.idx[ti][s] >> ((s & 1) * 16));
+                } else {
+                    acc2[ti] = mma_dense<DT>(a2.v[0][ti][s], bf.lo, acc2[ti]);
+                    acc2[ti] = mma_dense<DT>(a2.v[1][ti][s], bf.hi, acc2[ti]);
+                }
+            }
+        }
+        __syncthreads();                                  // the chunk buffer is free again
+        a1 = a1n;
+    }
+
+    // ---- output: bias + residual + activation in fp32, one rounding; each 32 x 32 tile crosses the wave's own LDS region
+    // (the input tile and the chunk buffer are dead: the loop ended with a barrier) and leaves as 16-byte runs
+    float *reg = reinterpret_cast<float *>(smem) + wave * (32 * kFuseRow);
+    const float floor2 = p.act2 == SS_ACT_RELU ? 0.f : -__builtin_inff();
+#pragma unroll
+    for (int ti = 0; ti < kMlpTiles; ti++) {
+        const int t = wave + 4 * ti;
+        if (t >= ntiles2) break;                          // uniform
+        const int rt = t >> 1, ct = t & 1;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const float4 bq = p.bias2 ? *reinterpret_cast<const float4 *>(p.bias2 + rt * 32 + 8 * q + 4 * g) : make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4 *>(reg + c * kFuseRow + 8 * q + 4 * g) =
+                make_float4(acc2[ti][4 * q + 0] + bq.x, acc2[ti][4 * q + 1] + bq.y, acc2[ti][4 * q + 2] + bq.z, acc2[ti][4 * q + 3] + bq.w);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int it = lane + 64 * j;
+            const int px = it >> 2, run = it & 3;
+            const int pg = n0 + ct * 32 + px, o = rt * 32 + run * 8;
+            const float4 lo = *reinterpret_cast<const float4 *>(reg + px * kFuseRow + run * 8);
+            const float4 hi = *reinterpret_cast<const float4 *>(reg + px * kFuseRow + run * 8 + 4);
+            if (pg >= p.P) continue;
+            float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            if (p.res2 != nullptr) {
+                const u32x4 rr = *reinterpret_cast<const u32x4 *>(p.res2 + (size_t)pg * p.Cout2 + o);
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    v[2 * e] += widen<DT>((uint16_t)(rr[e] & 0xFFFFu));
+                    v[2 * e + 1] += widen<DT>((uint16_t)(rr[e] >> 16));
+                }
+            }
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                float a = v[2 * e], b = v[2 * e + 1];
+                if (p.act2 == SS_ACT_GELU) { a = a * normal_cdf(a); b = b * normal_cdf(b); }
+                else { a = a < floor2 ? 0.f : a; b = b < floor2 ? 0.f : b; }
+                w[e] = cvt_pack2<DT>(a, b);
+            }
+            *reinterpret_cast<uint4 *>(p.y2 + (size_t)pg * p.Cout2 + o) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
+template <int DT, bool SPARSE>
+static int launch_mlp(const MlpParams &p, hipStream_t s)
+{
+    const long long blocks = ((long long)p.P + 63) / 64;
+    if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
+    size_t smem = (size_t)64 * (p.Cin + 8) * 2 + (size_t)64 * (128 + 4) * 2;
+    const size_t epi = 4 * kFuseRegion;
+    if (smem < epi) smem = epi;
+    mlp_kernel<DT, SPARSE><<<dim3((unsigned)blocks), dim3(256), smem, s>>>(p);
+    return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP = false, bool SPEC = false, bool FUSE = false>
@@ -1231,7 +1469,14 @@ static int fused_entry(const ss_weight_desc *d1, const void *x, int32_t N, int32
     if (st != SS_OK) return st;
     if (is_byte_type(d1->dtype) || d2->dtype != d1->dtype) return SS_ERR_UNSUPPORTED;
     if (d2->kh != 1 || d2->kw != 1 || d2->cin != d1->cout) return SS_ERR_INVALID_ARG;
-    if (d1->cout % 32 != 0 || d1->cout > 256 || d2->cout % 32 != 0 || d1->kh * d1->kw == 1) return SS_ERR_UNSUPPORTED;
+    const bool mlp = d1->kh * d1->kw == 1;        // 1x1 -> 1x1: the inverted-bottleneck kernel
+    if (mlp) {
+        if (d1->cin % 32 != 0 || d1->cin > 32 * kMlpKs1 || d1->cout % 128 != 0 || d2->cout % 32 != 0 ||
+            d2->cout > 64 * kMlpTiles)
+            return SS_ERR_UNSUPPORTED;
+    } else if (d1->cout % 32 != 0 || d1->cout > 256 || d2->cout % 32 != 0) {
+        return SS_ERR_UNSUPPORTED;
+    }
     if (!x || !w1 || !w2 || !y) return SS_ERR_INVALID_ARG;
     if (N <= 0 || H <= 0 || Wd <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return SS_ERR_INVALID_ARG;
     for (int a : {act1, act2})
@@ -1248,6 +1493,27 @@ static int fused_entry(const ss_weight_desc *d1, const void *x, int32_t N, int32
     const TileDims t1 = tile_dims(d1), t2 = tile_dims(d2);
     if ((SPARSE ? packed_size(t1) : dense_size(t1)) >= (1ull << 31) || (SPARSE ? packed_size(t2) : dense_size(t2)) >= (1ull << 31))
         return SS_ERR_UNSUPPORTED;
+    if (mlp) {
+        if (sh != 1 || sw != 1 || ph != 0 || pw != 0) return SS_ERR_UNSUPPORTED;
+        if (bias1 && !aligned(bias1, 16)) return SS_ERR_INVALID_ARG;
+        MlpParams m{};
+        m.x = static_cast<const uint16_t *>(x);
+        m.a1_vals = static_cast<const uint8_t *>(w1) + kHeaderBytes;
+        m.a1_meta = reinterpret_cast<const uint32_t *>(m.a1_vals + (size_t)t1.Mt * t1.Ks * 1024);
+        m.a2_vals = static_cast<const uint8_t *>(w2) + kHeaderBytes;
+        m.a2_meta = reinterpret_cast<const uint32_t *>(m.a2_vals + (size_t)t2.Mt * t2.Ks * 1024);
+        m.bias1 = bias1; m.bias2 = bias2;
+        m.res2 = static_cast<const uint16_t *>(residual);
+        m.y2 = static_cast<uint16_t *>(y);
+        m.P = (int)P; m.Cin = d1->cin; m.Cmid = d1->cout; m.Cout2 = d2->cout;
+        m.Ks1 = t1.Ks; m.Kp1 = t1.Kp; m.Ks2 = t2.Ks; m.Kp2 = t2.Kp; m.Mt2 = t2.Mt; m.act1 = act1; m.act2 = act2;
+        m.a1_bytes = (unsigned)((size_t)t1.Mt * t1.Ks * (SPARSE ? 1024 : 2048));
+        m.meta1_bytes = SPARSE ? (unsigned)((size_t)t1.Mt * t1.Kp * 256) : 4u;
+        m.a2_bytes = (unsigned)((size_t)t2.Mt * t2.Ks * (SPARSE ? 1024 : 2048));
+        m.meta2_bytes = SPARSE ? (unsigned)((size_t)t2.Mt * t2.Kp * 256) : 4u;
+        hipStream_t ms = static_cast<hipStream_t>(stream);
+        return d1->dtype == SS_F16 ? launch_mlp<SS_F16, SPARSE>(m, ms) : launch_mlp<SS_BF16, SPARSE>(m, ms);
+    }
     ConvParams p{};
     p.x = static_cast<const uint16_t *>(x);
     p.a_vals = static_cast<const uint8_t *>(w1) + kHeaderBytes;

@@ -61,6 +61,11 @@ PAIRS = [
     _pair(2, 15, 13, 32, 96, 160, s=2, seed=4),                      # stride 2, cout1 = 96 inside a 128-row tile, 5 row tiles of the second layer
     _pair(2, 10, 10, 24, 64, 96, korder=wl.K_RSC, seed=5),           # channels-last flattening of the first layer
     _pair(1, 12, 12, 40, 128, 64, k=5, p=2, korder=wl.K_RSC, act1=wl.ACT_NONE, act2=wl.ACT_GELU, dtype=wl.F16, seed=6),
+    # 1x1 -> activation -> 1x1: the inverted bottleneck (intermediate 4x wide, produced and consumed 128 channels at a time)
+    _pair(2, 13, 11, 96, 384, 96, k=1, p=0, act1=wl.ACT_GELU, act2=wl.ACT_NONE, seed=7),      # ConvNeXt block shape, ragged pixels
+    _pair(1, 9, 9, 32, 128, 32, k=1, p=0, dtype=wl.F16, seed=8),                                 # one step, one chunk, one row tile
+    _pair(3, 8, 8, 128, 512, 128, k=1, p=0, seed=9),                                            # the widest supported ends
+    _pair(2, 7, 10, 64, 256, 96, k=1, p=0, act1=wl.ACT_RELU, act2=wl.ACT_GELU, dtype=wl.F16, seed=10),   # 3 row tiles of the second layer over 4 waves
 ]
 
 
@@ -80,7 +85,9 @@ def force_tile():
         os.environ["SS_TILE"] = old
 
 
-def _tiles_for(cmid):
+def _tiles_for(cmid, k=3):
+    if k == 1:
+        return [None]                  # the 1x1 -> 1x1 kernel has a single shape
     return [None] + ([0, 1] if cmid <= 64 else []) + ([2, 4] if cmid <= 128 else []) + [3, 5]
 
 
@@ -94,7 +101,7 @@ def test_fused_pair_matches_oracle_chain(ss, force_tile, pair, with_res):
         rng = np.random.Generator(np.random.PCG64(5 + L1.seed))
         res_bits = wl.to_bits(rng.standard_normal((L1.N, L1.Ho, L1.Wo, L2.cout), dtype=np.float32), L1.dtype)
     t_bits, ref = _oracle_pair(L1, L2, d1, d2, res_bits)
-    for tile in _tiles_for(L1.cout):
+    for tile in _tiles_for(L1.cout, L1.kh):
         force_tile(tile)
         for sparse in (True, False):
             y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
@@ -151,4 +158,33 @@ def test_fused_argument_errors(ss):
     d512 = ss.make_desc(128, 512, 1, 1, L1.dtype, wl.K_CRS)
     p512 = torch.zeros(ss.ss_packed_bytes(d512), dtype=torch.uint8, device="cuda")
     assert status(lambda: ss.ss_conv2d_pw_fused_fwd(wide, x, pw, None, (1, 1), (1, 1), 0, d512, p512)) == ss.SS_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+
+
+def test_inverted_bottleneck_is_bit_exact_on_integers(ss):
+    L1, L2 = _pair(2, 9, 8, 64, 256, 96, k=1, p=0, act1=wl.ACT_RELU, act2=wl.ACT_NONE, dtype=wl.F16, seed=12)
+    d1, d2 = wl.make_small_int_inputs(L1, seed=1), wl.make_small_int_inputs(L2, seed=2)
+    d2["W"] = wl.to_bits((wl.from_bits(d2["W"], wl.F16) * (np.arange(L2.cin) % 8 == 0)).astype(np.float32), wl.F16)
+    res_bits = wl.to_bits(np.random.default_rng(3).integers(-3, 4, size=(L1.N, L1.Ho, L1.Wo, L2.cout)).astype(np.float32), wl.F16)
+    t_bits, ref = _oracle_pair(L1, L2, d1, d2, res_bits)
+    assert np.abs(ref).max() <= 2048 and np.abs(oracle.bits_to_double(t_bits, wl.F16)).max() <= 2048
+    for sparse in (True, False):
+        y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
+        assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref), sparse
+        assert np.array_equal(host_bits(y), host_bits(y_sep))
+
+
+def test_inverted_bottleneck_limits(ss):
+    def status(fn):
+        with pytest.raises(ss.SSError) as e:
+            fn()
+        return e.value.status
+    x = torch.zeros((1, 4, 4, 160), dtype=torch.float16, device="cuda")
+    for cin, cmid, cout in ((160, 256, 64), (64, 192, 64), (64, 256, 160)):     # cin > 128, cmid % 128, cout > 128
+        d1 = ss.make_desc(cmid, cin, 1, 1, wl.F16, wl.K_CRS)
+        d2 = ss.make_desc(cout, cmid, 1, 1, wl.F16, wl.K_CRS)
+        p1 = torch.zeros(ss.ss_packed_bytes(d1), dtype=torch.uint8, device="cuda")
+        p2 = torch.zeros(ss.ss_packed_bytes(d2), dtype=torch.uint8, device="cuda")
+        xi = x[..., :cin].contiguous()
+        assert status(lambda: ss.ss_conv2d_pw_fused_fwd(d1, xi, p1, None, (1, 1), (0, 0), 0, d2, p2)) == ss.SS_ERR_UNSUPPORTED
     torch.cuda.synchronize()
