@@ -161,17 +161,21 @@ __device__ __forceinline__ float widen(uint16_t bits)
         return __builtin_bit_cast(float, (uint32_t)bits << 16);
 }
 
-// Standard normal CDF Phi(v) = erfc(-v / sqrt 2) / 2 for the GELU z * Phi(z).  erfc by the rational approximation
-// 7.1.26 of Abramowitz & Stegun (erfc(x) = t (a1 + t (a2 + ... a5 t)) exp(-x^2), t = 1 / (1 + p x), x >= 0; absolute
-// error below 1.5e-7, i.e. at fp32 round-off and three orders below the 16-bit output's), which costs a third of
-// the library erfc in an epilogue that otherwise only adds and rounds.
-__device__ __forceinline__ float normal_cdf(float v)
+// GELU z * Phi(z) with the exact standard normal CDF Phi(z) = erfc(-z / sqrt 2) / 2.  erfc by the rational
+// approximation 7.1.26 of Abramowitz & Stegun (erfc(x) = t (a1 + t (a2 + ... a5 t)) exp(-x^2), t = 1 / (1 + p x),
+// x >= 0; absolute error below 1.5e-7, i.e. at fp32 round-off and three orders below the 16-bit output's), which
+// costs a third of the library erfc in an epilogue that otherwise only adds and rounds.  With h = Phi(-|z|):
+//     z >= 0:  z (1 - h) = z - |z| h        z < 0:  z h = -|z| h        i.e.  gelu(z) = max(z, 0) - |z| h,
+// which keeps the lower tail's relative accuracy (no 1 - erf cancellation) and needs no select.  The constants carry
+// the 1/sqrt 2 of the argument and the 1/2 of Phi; exp(-z^2 / 2) is one exp2.  (A NaN stays a NaN.)
+__device__ __forceinline__ float gelu_erfc(float z)
 {
-    const float x = fabsf(v) * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
-    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-    const float half_erfc = 0.5f * poly * __expf(-x * x);     // Phi(-|v|)
-    return v < 0.f ? half_erfc : 1.0f - half_erfc;            // (a NaN falls through to 1 - NaN = NaN)
+    const float a = fabsf(z);
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f * 0.70710678118654752f, a, 1.0f));
+    const float poly = t * (0.5f * 0.254829592f + t * (0.5f * -0.284496736f + t * (0.5f * 1.421413741f +
+                       t * (0.5f * -1.453152027f + t * (0.5f * 1.061405429f)))));
+    const float e = __builtin_amdgcn_exp2f(a * a * (-0.5f * 1.44269504088896341f));      // exp(-z^2 / 2)
+    return __builtin_fmaf(-a, poly * e, fmaxf(z, 0.f));
 }
 
 // How the [pixels x reduction-chunk] slice of the unfolded input is built in LDS:
@@ -740,7 +744,7 @@ void conv_kernel(ConvParams p)
     // ReLU when relu_floor = 0, identity when -inf (a NaN passes through); GELU = z * Phi(z) with the exact normal
     // CDF, written with erfc so that the lower tail keeps its relative accuracy
     auto relu_or_id = [&](float v) { return v < relu_floor ? 0.f : v; };
-    auto gelu = [](float v) { return v * normal_cdf(v); };
+    auto gelu = [](float v) { return gelu_erfc(v); };
     if (!with_res) {
         constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
         uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
@@ -1049,7 +1053,7 @@ void mlp_kernel(MlpParams p)
         }
     };
 
-    Row1 a1, a1n;
+    Row1 a1;
     Row2 a2;
     load_row1(a1, wave);
     // ---- the input tile: 64 pixel rows of Cin channels, 16-byte vectors, zeros past the last pixel
@@ -1106,13 +1110,13 @@ void mlp_kernel(MlpParams p)
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     const float z = acc1[tn][4 * q + e] + bv[e];
-                    r[e] = p.act1 == SS_ACT_GELU ? z * normal_cdf(z) : (z < floor1 ? 0.f : z);
+                    r[e] = p.act1 == SS_ACT_GELU ? gelu_erfc(z) : (z < floor1 ? 0.f : z);
                 }
                 *reinterpret_cast<uint2 *>(Cs + (tn * 32 + c) * CROW + wave * 32 + 8 * q + 4 * g) =
                     make_uint2(cvt_pack2<DT>(r[0], r[1]), cvt_pack2<DT>(r[2], r[3]));
             }
         }
-        if (mc + 1 < nchunks) load_row1(a1n, (mc + 1) * 4 + wave);      // in flight while the second contraction runs
+        if (mc + 1 < nchunks) load_row1(a1, (mc + 1) * 4 + wave);       // (its registers are free) in flight while the second contraction runs
         __syncthreads();
         // ---- second contraction: this chunk's 128 intermediate channels into the output accumulators
 #pragma unroll
@@ -1137,7 +1141,6 @@ void mlp_kernel(MlpParams p)
             }
         }
         __syncthreads();                                  // the chunk buffer is free again
-        a1 = a1n;
     }
 
     // ---- output: bias + residual + activation in fp32, one rounding; each 32 x 32 tile crosses the wave's own LDS region
@@ -1176,7 +1179,7 @@ void mlp_kernel(MlpParams p)
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 float a = v[2 * e], b = v[2 * e + 1];
-                if (p.act2 == SS_ACT_GELU) { a = a * normal_cdf(a); b = b * normal_cdf(b); }
+                if (p.act2 == SS_ACT_GELU) { a = gelu_erfc(a); b = gelu_erfc(b); }
                 else { a = a < floor2 ? 0.f : a; b = b < floor2 ? 0.f : b; }
                 w[e] = cvt_pack2<DT>(a, b);
             }
