@@ -30,7 +30,7 @@ SPARSE_INT8_PEAK_TOPS = 10000.0     # 2 x the published dense int8 peak (5.0 POP
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the sparse kernel on configs[1], from the rocprofv3 counter runs summarised in
 # profiles/conv_kernel_cfg1_hbm_traffic.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (factors from a streaming copy).
-CFG1_TRAFFIC_BYTES = int((2.0 * 4315.0 + 1.0 * 3136.0) * 1024)
+CFG1_TRAFFIC_BYTES = int((2.0 * 4328.0 + 1.0 * 3136.0) * 1024)
 
 
 def _to_dev(bits, dtype, torch, ss):
