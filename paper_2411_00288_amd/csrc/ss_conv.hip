@@ -273,7 +273,7 @@ constexpr int min_waves_per_simd(int tm, int tn, bool big_stage)
 // bottleneck without the intermediate tensor's round trip through memory.
 template <int DT, bool SPARSE, int WAVES_M, int WAVES_N, int TM, int TN, int MODE, int KH, int KW, bool DEEP, bool SPEC, bool FUSE = false>
 __global__ __launch_bounds__((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64)
-__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : ((DT == SS_F8 && !SPARSE && MODE == MODE_VEC && TM * TN == 2) ? 3 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8)))))
+__attribute__((amdgpu_waves_per_eu(DEEP ? 1 : (((DT == SS_F8 || FUSE) && !SPARSE && MODE == MODE_VEC && TM * TN == 2) ? 3 : min_waves_per_simd(TM, TN, MODE == MODE_TAPS || MODE == MODE_VEC8)))))
 void conv_kernel(ConvParams p)
 {
     using CS = ChunkShape<MODE, KH, KW, DEEP>;
