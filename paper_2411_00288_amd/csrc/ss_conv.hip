@@ -994,6 +994,7 @@ void mlp_kernel(MlpParams p)
     const int XROW = p.Cin + 8;                           // halfs per pixel row of the input tile (16-byte aligned rows)
     uint16_t *Xs = smem;
     uint16_t *Cs = smem + BN * XROW;
+    float *b1s = reinterpret_cast<float *>(Cs + BN * CROW);       // the first layer's bias, all Cmid values
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1004,10 +1005,9 @@ void mlp_kernel(MlpParams p)
     const __amdgpu_buffer_rsrc_t r2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a2_vals), 0, (int)p.a2_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t m2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a2_meta), 0, (int)p.meta2_bytes, kRsrcFlags);
 
-    struct Row1 {                                         // one 32-row tile of the first layer: all its reduction steps, and its bias
+    struct Row1 {                                         // one 32-row tile of the first layer: all its reduction steps
         u32x4 v[SPARSE ? 1 : 2][kMlpKs1];
         uint32_t idx[kMlpKs1];
-        float4 b[4];
     };
     auto load_row1 = [&](Row1 &r, int mt) {
 #pragma unroll
@@ -1022,9 +1022,6 @@ void mlp_kernel(MlpParams p)
                 r.v[1][s] = __builtin_amdgcn_raw_buffer_load_b128(r1, (int)off, 1024, 0);
             }
         }
-#pragma unroll
-        for (int q = 0; q < 4; q++)
-            r.b[q] = p.bias1 ? *reinterpret_cast<const float4 *>(p.bias1 + mt * 32 + 8 * q + 4 * g) : make_float4(0.f, 0.f, 0.f, 0.f);
     };
     // the second layer's weights for this wave's output tiles and the 4 reduction steps of one chunk
     struct Row2 {
@@ -1066,7 +1063,20 @@ void mlp_kernel(MlpParams p)
             if (pg < p.P) v = *reinterpret_cast<const u32x4 *>(p.x + (size_t)pg * p.Cin + u * 8);
             *reinterpret_cast<u32x4 *>(Xs + px * XROW + u * 8) = v;
         }
+        for (int i = tid; i < p.Cmid; i += 256) b1s[i] = p.bias1 ? p.bias1[i] : 0.f;
     }
+    // this workgroup's residual, in the output stage's thread -> (pixel, run) mapping: fetched now, used at the very end
+    u32x4 rres[kMlpTiles][2];
+#pragma unroll
+    for (int ti = 0; ti < kMlpTiles; ti++)
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const int t = wave + 4 * ti, it = lane + 64 * j;
+            const int pg = n0 + (t & 1) * 32 + (it >> 2);
+            rres[ti][j] = u32x4{0u, 0u, 0u, 0u};
+            if (p.res2 != nullptr && t < p.Mt2 * 2 && pg < p.P)
+                rres[ti][j] = *reinterpret_cast<const u32x4 *>(p.res2 + (size_t)pg * p.Cout2 + (t >> 1) * 32 + (it & 3) * 8);
+        }
     f32x16 acc2[kMlpTiles];
 #pragma unroll
     for (int ti = 0; ti < kMlpTiles; ti++)
@@ -1103,7 +1113,8 @@ void mlp_kernel(MlpParams p)
         }
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const float bv[4] = {a1.b[q].x, a1.b[q].y, a1.b[q].z, a1.b[q].w};
+            const float4 bq1 = *reinterpret_cast<const float4 *>(b1s + (mc * 4 + wave) * 32 + 8 * q + 4 * g);
+            const float bv[4] = {bq1.x, bq1.y, bq1.z, bq1.w};
 #pragma unroll
             for (int tn = 0; tn < 2; tn++) {
                 float r[4];
@@ -1168,7 +1179,7 @@ void mlp_kernel(MlpParams p)
             if (pg >= p.P) continue;
             float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
             if (p.res2 != nullptr) {
-                const u32x4 rr = *reinterpret_cast<const u32x4 *>(p.res2 + (size_t)pg * p.Cout2 + o);
+                const u32x4 rr = rres[ti][j];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     v[2 * e] += widen<DT>((uint16_t)(rr[e] & 0xFFFFu));
@@ -1193,7 +1204,7 @@ static int launch_mlp(const MlpParams &p, hipStream_t s)
 {
     const long long blocks = ((long long)p.P + 63) / 64;
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
-    size_t smem = (size_t)64 * (p.Cin + 8) * 2 + (size_t)64 * (128 + 4) * 2;
+    size_t smem = (size_t)64 * (p.Cin + 8) * 2 + (size_t)64 * (128 + 4) * 2 + (size_t)p.Cmid * 4;
     const size_t epi = 4 * kFuseRegion;
     if (smem < epi) smem = epi;
     mlp_kernel<DT, SPARSE><<<dim3((unsigned)blocks), dim3(256), smem, s>>>(p);
