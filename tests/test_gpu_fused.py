@@ -188,3 +188,58 @@ def test_inverted_bottleneck_limits(ss):
         xi = x[..., :cin].contiguous()
         assert status(lambda: ss.ss_conv2d_pw_fused_fwd(d1, xi, p1, None, (1, 1), (0, 0), 0, d2, p2)) == ss.SS_ERR_UNSUPPORTED
     torch.cuda.synchronize()
+
+
+def test_fused_and_8_bit_launches_replay_in_a_hip_graph(ss):
+    """The prepared launches of the fused pair, the inverted bottleneck and the 8-bit convolution, captured in one HIP
+    graph and replayed on changing input contents (eager work and synchronisation in between): every replay equals
+    the eager result bit for bit."""
+    L1, L2 = _pair(2, 12, 12, 64, 64, 128, seed=31)
+    M1, M2 = _pair(2, 12, 12, 96, 384, 96, k=1, p=0, act1=wl.ACT_GELU, act2=wl.ACT_NONE, seed=32)
+    Q = wl.Layer("q", N=2, H=12, W=12, cin=64, cout=96, kh=3, kw=3, stride=1, pad=1, dtype=wl.I8, korder=wl.K_CRS,
+                 act=wl.ACT_RELU, mask="logits", seed=33)
+    launches, outs, inputs, eagers = [], [], [], []
+    for A, B in ((L1, L2), (M1, M2)):
+        d1, d2 = wl.make_inputs(A), wl.make_inputs(B)
+        ds1 = ss.make_desc(A.cout, A.cin, A.kh, A.kw, A.dtype, A.korder)
+        ds2 = ss.make_desc(B.cout, B.cin, 1, 1, B.dtype, B.korder)
+        x = dev_bits(d1["x"], A.dtype)
+        p1 = ss.ss_mask_compress(ds1, dev_bits(d1["W"], A.dtype), torch.from_numpy(d1["M"]).cuda())
+        p2 = ss.ss_mask_compress(ds2, dev_bits(d2["W"], B.dtype), torch.from_numpy(d2["M"]).cuda())
+        b1, b2 = torch.from_numpy(d1["bias"]).cuda(), torch.from_numpy(d2["bias"]).cuda()
+        res = torch.randn((A.N, A.Ho, A.Wo, B.cout), device="cuda").to(x.dtype)
+        st, pd = (A.stride,) * 2, (A.pad,) * 2
+        launch, y = ss.prepare_conv2d_pw_fused(ds1, x, p1, b1, st, pd, A.act, ds2, p2, b2, res, B.act)
+        launches.append(launch); outs.append(y); inputs.append(x)
+        eagers.append(lambda ds1=ds1, x=x, p1=p1, b1=b1, st=st, pd=pd, A=A, ds2=ds2, p2=p2, b2=b2, res=res, B=B:
+                      ss.ss_conv2d_pw_fused_fwd(ds1, x, p1, b1, st, pd, A.act, ds2, p2, b2, res, B.act))
+    dq = wl.make_inputs_q8(Q)
+    dsq = ss.make_desc(Q.cout, Q.cin, 3, 3, wl.I8, Q.korder)
+    xq = torch.from_numpy(dq["x"]).cuda()
+    pq = ss.ss_mask_compress(dsq, torch.from_numpy(dq["W"]).cuda(), torch.from_numpy(dq["M"]).cuda())
+    sq, bq = torch.from_numpy(dq["scale"]).cuda(), torch.from_numpy(dq["bias"]).cuda()
+    launch, y = ss.prepare_conv2d_q8(dsq, xq, pq, sq, bq, (1, 1), (1, 1), Q.act)
+    launches.append(launch); outs.append(y); inputs.append(xq)
+    eagers.append(lambda: ss.ss_conv2d_q8_fwd(dsq, xq, pq, sq, bq, (1, 1), (1, 1), Q.act))
+    for l in launches:
+        l()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for l in launches:
+                l()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for x in inputs:
+            x.copy_(torch.roll(x, shifts=rep + 1, dims=2))          # new contents, same buffers
+        want = [e().clone() for e in eagers]
+        torch.cuda.synchronize()
+        for y in outs:
+            y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for y, w in zip(outs, want):
+            assert torch.equal(y.view(torch.int16), w.view(torch.int16)), f"replay {rep}"
