@@ -7,8 +7,12 @@ already resident in device memory; the weight compressor is a one-off per weight
 timed separately.  The dense twin is timed the same way for the speed-up ratio, and the CPU
 oracle is timed on the host cores as a reported baseline.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail | --trunk]   (--table: per-layer report,
-                                                                          --tail: fused residual tail report)
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail | --trunk | --fused | --q8]
+        --table  per-layer report of configs 0-2, the ResNet-50 stack and ConvNeXt-T stage 1 (--cold, --only)
+        --tail   the fused residual / activation tail against a separate pass
+        --trunk  the ResNet-50 convolution trunk chained in one HIP graph, images/s
+        --fused  a k x k convolution and the 1x1 after it (or the two 1x1 of a ConvNeXt block) in one kernel
+        --q8     the int8 / FP8 precision points
 """
 from __future__ import annotations
 
