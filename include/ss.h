@@ -16,7 +16,8 @@
  * General conventions
  *   - Every function returns an int status: SS_OK (0) or a negative SS_ERR_* code.  Nothing throws.
  *   - Unless a parameter is marked [host], every data pointer is a DEVICE pointer.  The caller
- *     owns every buffer; the library never allocates or frees device memory and keeps no state.
+ *     owns every buffer; the library never allocates or frees device memory.  Its only state is a per-device
+ *     record of which kernels have had their shared-memory limit raised (set once, at a kernel's first launch).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The convolution
  *     calls only enqueue work on it and return; ss_mask_compress additionally waits for the
  *     stream once, because it reports the mask's validity.
@@ -121,7 +122,7 @@ int ss_dense_bytes(const ss_weight_desc *desc, size_t *dense_bytes /*[host] out*
  * Weight compressor (Fig. 1; Sec. 3.1 Eq. 2 for the validity rule).
  *   W       [cout][K] elements of desc->dtype (16-bit, or int8), flattening per desc->korder   (read only)
  *   M       [cout][K] bytes, each 0 or 1                                    (read only)
- *   packed  ss_packed_bytes(desc) bytes, 256-byte aligned                   (written)
+ *   packed  ss_packed_bytes(desc) bytes, 16-byte aligned                    (written)
  *   bad_row_group [host, optional] two int32: on SS_ERR_BAD_MASK receives the row and the block
  *           index of the first (row-major) invalid block.
  * Values are copied bit for bit: a kept weight that is -0, NaN or subnormal is preserved.
@@ -159,6 +160,19 @@ int ss_mask_decompress(const ss_weight_desc *desc, const void *packed, void *W_m
  */
 int ss_dense_pack(const ss_weight_desc *desc, const void *W, const uint8_t *M, void *dense,
                   void *stream);
+
+/*
+ * Set-up-time check that a weight buffer belongs to a descriptor.  The convolution calls are asynchronous and
+ * trust their weight operand: they read it with the sizes the descriptor implies and never look at its header.
+ * This call reads the buffer's 256-byte header back (one stream synchronisation, like ss_mask_compress) and returns
+ *   SS_ERR_INVALID_ARG  when the buffer was not written by ss_mask_compress / ss_mask_update_compress (sparse != 0)
+ *                       or ss_dense_pack (sparse == 0), or was written for another cout, cin, kh, kw, dtype or
+ *                       korder than desc states (e.g. a dense operand offered to ss_conv2d_fwd);
+ *   SS_ERR_BAD_MASK     when it was written by a compression call that rejected its mask (Eq. 2 violated);
+ *   SS_OK               otherwise.
+ * Call it once per weight buffer, after packing and before the first convolution.
+ */
+int ss_weights_check(const ss_weight_desc *desc, const void *weights, int32_t sparse, void *stream);
 
 /*
  * Scratch the convolution needs for the given problem (fp32 partial sums when the reduction is

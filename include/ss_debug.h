@@ -1,0 +1,27 @@
+/*
+ * ss_debug.h -- test hooks of the 2:4 sparse convolution library.  Not part of the product interface: nothing a
+ * caller needs for correct results or for speed lives here.  The hooks exist so that tests can reach every kernel
+ * variant the library would otherwise choose by problem size.
+ */
+#ifndef SS_DEBUG_H_
+#define SS_DEBUG_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Forces the workgroup tile of the convolution entry points (ss_conv2d_*_fwd) to the kernel variant with this id
+ * for all later calls of the process; a negative id returns the choice to the library.  Ids the problem's staging
+ * mode has no kernel for fall back to the library's choice.  Process-wide, read with a relaxed atomic load at every
+ * launch; meant for single-threaded tests.  Always returns SS_OK.  [host]
+ */
+int ss_debug_force_tile(int32_t id);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif

@@ -23,7 +23,9 @@ SS_ACT_NONE, SS_ACT_RELU, SS_ACT_GELU = 0, 1, 2
 EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_compress", "ss_mask_decompress",
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
-           "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd"]
+           "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd",
+           "ss_weights_check"]
+DEBUG_EXPORTS = ["ss_debug_force_tile"]          # include/ss_debug.h: test hooks
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -69,7 +71,9 @@ def _load() -> ctypes.CDLL:
     fused_args = [dp, vp, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, dp, vp, vp, vp, i32, vp, vp]
     lib.ss_conv2d_pw_fused_fwd.argtypes = fused_args
     lib.ss_conv2d_pw_fused_dense_fwd.argtypes = fused_args
-    for name in EXPORTS[1:]:
+    lib.ss_weights_check.argtypes = [dp, vp, i32, vp]
+    lib.ss_debug_force_tile.argtypes = [i32]
+    for name in EXPORTS[1:] + DEBUG_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -200,6 +204,35 @@ def ss_dense_pack(desc: ss_weight_desc, W: torch.Tensor, M: torch.Tensor | None,
     return dense
 
 
+def ss_weights_check(desc: ss_weight_desc, weights: torch.Tensor, sparse: bool = True, stream=None) -> None:
+    """Raises unless `weights` was written for `desc` by the matching packing call (and, for the sparse form, with a
+    valid mask).  One stream synchronisation; call once per buffer at set-up."""
+    need = ss_packed_bytes(desc) if sparse else ss_dense_bytes(desc)
+    if weights is None or weights.numel() * weights.element_size() < need:
+        raise SSError(SS_ERR_INVALID_ARG, "ss_weights_check: buffer smaller than the descriptor's size query")
+    st = _lib.ss_weights_check(ctypes.byref(desc), _dev_ptr(weights, "weights"), 1 if sparse else 0, _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_weights_check")
+
+
+def ss_debug_force_tile(tile_id: int) -> None:
+    """Test hook (include/ss_debug.h): force the convolution kernels' tile variant; negative = library's choice."""
+    _lib.ss_debug_force_tile(int(tile_id))
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _check_operands(what, desc, wbuf, bias, sparse):
+    """Sizes the asynchronous calls rely on and cannot check themselves: a short buffer would be read past its end."""
+    need = ss_packed_bytes(desc) if sparse else ss_dense_bytes(desc)
+    if _nbytes(wbuf) < need:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: weight buffer holds {_nbytes(wbuf)} bytes, the descriptor needs {need}")
+    if bias is not None and bias.numel() < desc.cout:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: bias holds {bias.numel()} values, cout is {desc.cout}")
+
+
 def ss_conv2d_workspace_bytes(desc, N, H, W, stride=(1, 1), pad=(0, 0)) -> int:
     out = ctypes.c_size_t(0)
     st = _lib.ss_conv2d_workspace_bytes(ctypes.byref(desc), N, H, W, stride[0], stride[1], pad[0], pad[1],
@@ -221,6 +254,7 @@ def _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream
     if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
     N, H, W, _ = x.shape
+    _check_operands(what, desc, wbuf, bias, "dense" not in what)
     shp = out_shape(desc, N, H, W, stride, pad)
     if shp[1] <= 0 or shp[2] <= 0:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")
@@ -303,6 +337,9 @@ def _q8_args(what, desc, x, wbuf, scale, bias, stride, pad, act, y, workspace):
     if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
     N, H, W, _ = x.shape
+    _check_operands(what, desc, wbuf, bias, "dense" not in what)
+    if scale is not None and scale.numel() < desc.cout:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: scale holds {scale.numel()} values, cout is {desc.cout}")
     shp = out_shape(desc, N, H, W, stride, pad)
     if shp[1] <= 0 or shp[2] <= 0:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")
@@ -366,6 +403,8 @@ def prepare_conv2d_pw_fused(desc1, x, w1, bias1, stride, pad, act1, desc2, w2, b
     if x is None or x.dim() != 4 or x.shape[3] != desc1.cin:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
     N, H, W, _ = x.shape
+    _check_operands(what, desc1, w1, bias1, sparse)
+    _check_operands(what, desc2, w2, bias2, sparse)
     shp1 = out_shape(desc1, N, H, W, stride, pad)
     if shp1[1] <= 0 or shp1[2] <= 0:
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")

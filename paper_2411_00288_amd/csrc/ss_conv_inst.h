@@ -1,0 +1,27 @@
+// Instantiates the convolution kernels for one operand type and one operand form (2:4-sparse or dense), named by the
+// including file through SS_INST_NAME / SS_INST_DT / SS_INST_SPARSE / SS_INST_FUSED.
+#include "ss_conv_kernel.h"
+
+#define SS_CAT2(a, b) a##b
+#define SS_CAT(a, b) SS_CAT2(a, b)
+
+namespace ss {
+
+int SS_CAT(conv_dispatch_, SS_INST_NAME)(const ss_weight_desc *desc, const ConvParams &p, hipStream_t s)
+{
+    return pick_mode<SS_INST_DT, SS_INST_SPARSE>(desc, p, s);
+}
+
+#if SS_INST_FUSED
+int SS_CAT(fused_dispatch_, SS_INST_NAME)(const ss_weight_desc *d1, const ConvParams &p, hipStream_t s)
+{
+    return fused_mode<SS_INST_DT, SS_INST_SPARSE>(d1, p, s);
+}
+
+int SS_CAT(mlp_dispatch_, SS_INST_NAME)(const MlpParams &p, hipStream_t s)
+{
+    return launch_mlp<SS_INST_DT, SS_INST_SPARSE>(p, s);
+}
+#endif
+
+}  // namespace ss

@@ -373,6 +373,25 @@ extern "C" int ss_mask_decompress(const ss_weight_desc *desc, const void *packed
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
 }
 
+extern "C" int ss_weights_check(const ss_weight_desc *desc, const void *weights, int32_t sparse, void *stream)
+{
+    int st = check_desc(desc, sparse != 0);
+    if (st != SS_OK) return st;
+    if (!weights || !aligned(weights, 16)) return SS_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t hdr[kHdrFirstBad + 1];
+    if (hipMemcpyAsync(hdr, weights, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess) return SS_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return SS_ERR_HIP;
+    const TileDims t = tile_dims(desc);
+    const uint32_t want[10] = {sparse ? kMagicSparse : kMagicDense, 1u, (uint32_t)desc->cout, (uint32_t)desc->cin,
+                               (uint32_t)desc->kh, (uint32_t)desc->kw, (uint32_t)desc->dtype, (uint32_t)desc->korder,
+                               (uint32_t)t.Mt, (uint32_t)t.Ks};
+    for (int i = 0; i < 10; i++)
+        if (hdr[i] != want[i]) return SS_ERR_INVALID_ARG;
+    if (sparse && hdr[kHdrFirstBad] != kNoBadBlock) return SS_ERR_BAD_MASK;
+    return SS_OK;
+}
+
 extern "C" int ss_dense_pack(const ss_weight_desc *desc, const void *W, const uint8_t *M, void *dense, void *stream)
 {
     int st = check_desc(desc, false);

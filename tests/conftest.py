@@ -21,3 +21,13 @@ def ss():
         pytest.skip("no GPU")
     import paper_2411_00288_amd as pkg
     return pkg
+
+
+@pytest.fixture
+def force_tile(ss):
+    """Forces the workgroup tile of the convolution kernels through the library's test hook (include/ss_debug.h);
+    the library's own choice is restored afterwards.  `None` = the library chooses."""
+    def setter(tid):
+        ss.ss_debug_force_tile(-1 if tid is None else int(tid))
+    yield setter
+    ss.ss_debug_force_tile(-1)

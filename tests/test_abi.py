@@ -9,8 +9,8 @@ import pytest
 ROOT = Path(__file__).resolve().parent.parent
 
 
-def declared_functions():
-    text = (ROOT / "include" / "ss.h").read_text()
+def declared_functions(header="ss.h"):
+    text = (ROOT / "include" / header).read_text()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ss_[a-z0-9_]+)\s*\(", text)))
 
@@ -23,6 +23,10 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/ss.h but not exported"
     assert sorted(ss.EXPORTS) == names
+    hooks = declared_functions("ss_debug.h")
+    for n in hooks:
+        assert hasattr(lib, n), f"{n} is declared in include/ss_debug.h but not exported"
+    assert sorted(ss.DEBUG_EXPORTS) == hooks
 
 
 def test_size_queries_and_descriptor_validation():

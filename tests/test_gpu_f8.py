@@ -1,5 +1,4 @@
 """GPU parity of the FP8 (OCP E4M3) precision point, through the C ABI."""
-import os
 
 import numpy as np
 import pytest
@@ -82,19 +81,6 @@ SHAPES = [
     _L(1, 7, 7, 512, 520, 3, p=1, seed=5),
     _L(2, 11, 12, 48, 64, 5, p=2, seed=2),
 ]
-
-
-@pytest.fixture
-def force_tile():
-    old = os.environ.get("SS_TILE")
-
-    def setter(tid):
-        os.environ["SS_TILE"] = str(tid)
-    yield setter
-    if old is None:
-        os.environ.pop("SS_TILE", None)
-    else:
-        os.environ["SS_TILE"] = old
 
 
 @pytest.mark.parametrize("L", SHAPES, ids=lambda L: L.name)

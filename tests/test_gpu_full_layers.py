@@ -1,6 +1,9 @@
-"""Full-size layers of the ResNet-50 (batch 64) and ConvNeXt-T stage-1 (batch 128) workloads, in the
-launch configuration the benchmark times, checked on sampled outputs that the oracle computes one by
-one (the full tensors would take the CPU minutes)."""
+"""Every unique layer shape of the ResNet-50 (batch 64) and ConvNeXt-T stage-1 (batch 128) workloads at full size,
+in the launch configuration the benchmark times, checked on sampled outputs that the oracle computes one by one
+(the full tensors would take the CPU minutes).  The sample is stratified: at least one output from every 64-channel
+x 64-pixel block of the output matrix, which is the granularity of the smallest workgroup tile, so every workgroup
+of whichever tile the library picks contributes a checked element; plus a uniform random draw and the first and
+last pixels."""
 import numpy as np
 import pytest
 import torch
@@ -14,14 +17,16 @@ pytestmark = pytest.mark.gpu
 NPTS = 4096
 
 
-def _pick(layers, names):
-    by = {l.name: l for l in layers}
-    return [by[n] for n in names]
+LAYERS = wl.resnet50_layers() + wl.convnext_t_stage1_layers()      # the 24 + 3 unique shapes (depthwise is not in the list)
 
 
-LAYERS = (_pick(wl.resnet50_layers(), ["stem_7x7_3_64_s2", "s1_c3_1x1_64_256", "s1_c2_3x3_64_64", "s2_c2_3x3_128_128_s2",
-                                        "s3_c2_3x3_256_256", "s4_c2_3x3_512_512", "s4_c1_1x1_2048_512", "s3_ds_1x1_512_1024_s2"])
-          + wl.convnext_t_stage1_layers())
+def stratified_indices(L, rng, block=64):
+    """Flat indices (pixel * cout + channel) with one uniformly drawn element per block x block tile of [P][cout]."""
+    nb_p, nb_o = -(-L.P // block), -(-L.cout // block)
+    bp, bo = np.meshgrid(np.arange(nb_p, dtype=np.int64), np.arange(nb_o, dtype=np.int64), indexing="ij")
+    pp = np.minimum(bp * block + rng.integers(0, block, size=bp.shape), L.P - 1)
+    oo = np.minimum(bo * block + rng.integers(0, block, size=bo.shape), L.cout - 1)
+    return (pp * L.cout + oo).reshape(-1)
 
 
 @pytest.mark.parametrize("L", LAYERS, ids=lambda L: L.name)
@@ -31,7 +36,7 @@ def test_full_size_layer_on_sampled_outputs(ss, L):
     y = run_gpu(ss, L, d, sparse=sparse)
     total = L.P * L.cout
     rng = np.random.default_rng(L.seed)
-    idx = np.unique(np.concatenate([rng.integers(0, total, size=NPTS),
+    idx = np.unique(np.concatenate([rng.integers(0, total, size=NPTS), stratified_indices(L, rng),
                                     np.arange(0, min(total, 64)),                  # first pixel's channels
                                     np.arange(total - 64, total)]))                # last pixel's channels
     ref = oracle.conv2d_points(d["x"], d["W"], d["M"], idx, cin=L.cin, kh=L.kh, kw=L.kw, korder=L.korder, dtype=L.dtype,

@@ -1,6 +1,5 @@
 """GPU parity of the fused k x k -> 1x1 pair (ss_conv2d_pw_fused_fwd and its dense twin) against the oracle, which
 evaluates the two layers one after the other with the intermediate rounded to the 16-bit type in between."""
-import os
 
 import numpy as np
 import pytest
@@ -51,7 +50,7 @@ def _run(ss, L1, L2, d1, d2, res_bits, sparse):
         t = ss.ss_conv2d_dense_fwd(dsc1, x, ss.ss_dense_pack(dsc1, W1, M1), b1, st, pd, L1.act)
         y_sep = ss.ss_conv2d_dense_res_fwd(dsc2, t, ss.ss_dense_pack(dsc2, W2, M2), b2, res, (1, 1), (0, 0), L2.act)
     torch.cuda.synchronize()
-    return y, y_sep
+    return y, y_sep, t
 
 
 PAIRS = [
@@ -67,22 +66,6 @@ PAIRS = [
     _pair(3, 8, 8, 128, 512, 128, k=1, p=0, seed=9),                                            # the widest supported ends
     _pair(2, 7, 10, 64, 256, 96, k=1, p=0, act1=wl.ACT_RELU, act2=wl.ACT_GELU, dtype=wl.F16, seed=10),   # 3 row tiles of the second layer over 4 waves
 ]
-
-
-@pytest.fixture
-def force_tile():
-    old = os.environ.get("SS_TILE")
-
-    def setter(tid):
-        if tid is None:
-            os.environ.pop("SS_TILE", None)
-        else:
-            os.environ["SS_TILE"] = str(tid)
-    yield setter
-    if old is None:
-        os.environ.pop("SS_TILE", None)
-    else:
-        os.environ["SS_TILE"] = old
 
 
 def _tiles_for(cmid, k=3):
@@ -104,7 +87,7 @@ def test_fused_pair_matches_oracle_chain(ss, force_tile, pair, with_res):
     for tile in _tiles_for(L1.cout, L1.kh):
         force_tile(tile)
         for sparse in (True, False):
-            y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
+            y, y_sep, t_gpu = _run(ss, L1, L2, d1, d2, res_bits, sparse)
             what = f"{L1.name} tile {tile} {'sparse' if sparse else 'dense'} res {with_res}"
             # The intermediate's rounding can differ in the last bit between the GPU's fp32 and the oracle's fp64 sums,
             # and such a difference then passes through the second layer: the bound is that of two layers.
@@ -113,6 +96,11 @@ def test_fused_pair_matches_oracle_chain(ss, force_tile, pair, with_res):
             rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
             assert rel <= 4e-3, f"{what}: rel-L2 {rel:.3e}"
             assert (np.abs(got - ref) <= 2e-2 * (np.abs(ref) + 1)).all(), what
+            # The second layer alone, at the single-layer bound: the oracle's 1x1 layer fed the intermediate the GPU
+            # itself produced (the separate first call's output, which the fused kernel keeps on chip bit for bit).
+            ref2 = oracle.conv2d(host_bits(t_gpu), d2["W"], d2["M"], cin=L2.cin, kh=1, kw=1, korder=L2.korder,
+                                 dtype=L2.dtype, bias=d2["bias"], act=L2.act, residual=res_bits)
+            check_close(y, ref2, what + " (second layer on the GPU's intermediate)")
             # against the library's own two separate calls the difference is one rounding of the output at most
             sep = y_sep.float().cpu().numpy().astype(np.float64)
             assert (np.abs(got - sep) <= 2.0 ** -7 * (np.abs(sep) + 1e-3)).all(), what
@@ -130,7 +118,7 @@ def test_fused_pair_is_bit_exact_on_integers(ss, force_tile, cmid):
     for tile in _tiles_for(cmid):
         force_tile(tile)
         for sparse in (True, False):
-            y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
+            y, y_sep, _t = _run(ss, L1, L2, d1, d2, res_bits, sparse)
             assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref), (tile, sparse)
             assert np.array_equal(host_bits(y), host_bits(y_sep))
 
@@ -169,7 +157,7 @@ def test_inverted_bottleneck_is_bit_exact_on_integers(ss):
     t_bits, ref = _oracle_pair(L1, L2, d1, d2, res_bits)
     assert np.abs(ref).max() <= 2048 and np.abs(oracle.bits_to_double(t_bits, wl.F16)).max() <= 2048
     for sparse in (True, False):
-        y, y_sep = _run(ss, L1, L2, d1, d2, res_bits, sparse)
+        y, y_sep, _t = _run(ss, L1, L2, d1, d2, res_bits, sparse)
         assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref), sparse
         assert np.array_equal(host_bits(y), host_bits(y_sep))
 

@@ -1,7 +1,6 @@
 """GPU parity of the 8-bit integer precision point, through the C ABI: packing bit for bit, the convolution against
 the oracle's exact integer sums (bit for bit where the 16-bit output can hold them, else to half an output ulp)."""
 import ctypes
-import os
 
 import numpy as np
 import pytest
@@ -136,19 +135,6 @@ def test_convolution_matches_oracle(ss, L):
     ref = _ref(L, d)
     check_q8(_run(ss, L, d, sparse=True), ref, f"{L.name} sparse")
     check_q8(_run(ss, L, d, sparse=False), ref, f"{L.name} dense")
-
-
-@pytest.fixture
-def force_tile():
-    old = os.environ.get("SS_TILE")
-
-    def setter(tid):
-        os.environ["SS_TILE"] = str(tid)
-    yield setter
-    if old is None:
-        os.environ.pop("SS_TILE", None)
-    else:
-        os.environ["SS_TILE"] = old
 
 
 @pytest.mark.parametrize("tile", TILE_IDS)

@@ -5,7 +5,6 @@ small-integer inputs, in place (y aliasing the residual), and at full size on a 
 outputs) in the launch configuration the benchmark uses.
 """
 import dataclasses
-import os
 
 import numpy as np
 import pytest
@@ -59,19 +58,6 @@ SHAPES = [
     _L(2, 12, 12, 96, 200, 2, s=2, act=wl.ACT_GELU, dtype=wl.BF16),
     _L(1, 11, 9, 12, 150, 3, p=1),                                    # gather fallback, cout % 8 != 0
 ]
-
-
-@pytest.fixture
-def force_tile():
-    old = os.environ.get("SS_TILE")
-
-    def set_tile(tid):
-        os.environ["SS_TILE"] = str(tid)
-    yield set_tile
-    if old is None:
-        os.environ.pop("SS_TILE", None)
-    else:
-        os.environ["SS_TILE"] = old
 
 
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])

@@ -1,10 +1,9 @@
 """Every instantiated tile shape / prefetch depth of the convolution kernel against the oracle.
 
-The library picks a tile from the problem size; `SS_TILE=<id>` (a tuning aid read at every launch)
+The library picks a tile from the problem size; the test hook `ss_debug_force_tile(id)` (include/ss_debug.h)
 forces one, so each shape is exercised here on problems that span several tiles in both
 directions and leave ragged tails, for every staging mode, sparse and dense.
 """
-import os
 
 import numpy as np
 import pytest
@@ -36,19 +35,6 @@ SHAPES = [
     _L(1, 9, 10, 20, 150, 3, p=1, korder=wl.K_RSC, seed=8),       # cin % 8 == 4 in the channels-last flattening
     _L(2, 14, 14, 192, 260, 3, p=1, seed=3),               # six chunks of 32 channels
 ]
-
-
-@pytest.fixture
-def force_tile():
-    old = os.environ.get("SS_TILE")
-
-    def setter(tid):
-        os.environ["SS_TILE"] = str(tid)
-    yield setter
-    if old is None:
-        os.environ.pop("SS_TILE", None)
-    else:
-        os.environ["SS_TILE"] = old
 
 
 @pytest.mark.parametrize("tile", TILE_IDS)
