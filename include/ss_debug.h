@@ -20,6 +20,14 @@ extern "C" {
  */
 int ss_debug_force_tile(int32_t id);
 
+/*
+ * Caps the number of workgroups the resident-grid convolution kernels launch (they normally launch one per compute
+ * unit and let each walk over several output tiles); 0 or a negative value removes the cap.  With a small cap a small
+ * test problem exercises the tile-to-tile hand-over that otherwise only large problems reach.  Process-wide, as
+ * above.  Always returns SS_OK.  [host]
+ */
+int ss_debug_limit_blocks(int32_t n);
+
 #ifdef __cplusplus
 }
 #endif

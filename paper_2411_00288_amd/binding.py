@@ -25,7 +25,7 @@ EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_com
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
            "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd",
            "ss_weights_check"]
-DEBUG_EXPORTS = ["ss_debug_force_tile"]          # include/ss_debug.h: test hooks
+DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks"]          # include/ss_debug.h: test hooks
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -73,6 +73,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_conv2d_pw_fused_dense_fwd.argtypes = fused_args
     lib.ss_weights_check.argtypes = [dp, vp, i32, vp]
     lib.ss_debug_force_tile.argtypes = [i32]
+    lib.ss_debug_limit_blocks.argtypes = [i32]
     for name in EXPORTS[1:] + DEBUG_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -218,6 +219,11 @@ def ss_weights_check(desc: ss_weight_desc, weights: torch.Tensor, sparse: bool =
 def ss_debug_force_tile(tile_id: int) -> None:
     """Test hook (include/ss_debug.h): force the convolution kernels' tile variant; negative = library's choice."""
     _lib.ss_debug_force_tile(int(tile_id))
+
+
+def ss_debug_limit_blocks(n: int) -> None:
+    """Test hook (include/ss_debug.h): cap the workgroups of the resident-grid kernels; 0 = no cap."""
+    _lib.ss_debug_limit_blocks(int(n))
 
 
 def _nbytes(t) -> int:

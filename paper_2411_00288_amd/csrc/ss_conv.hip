@@ -33,6 +33,23 @@ namespace ss {
 
 static std::atomic<int> g_forced_tile{-1};
 int forced_tile() { return g_forced_tile.load(std::memory_order_relaxed); }
+static std::atomic<int> g_block_limit{0};
+int block_limit() { return g_block_limit.load(std::memory_order_relaxed); }
+
+int compute_units()
+{
+    static std::atomic<int> cached[64];                   // 0 = not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    if (dev >= 0 && dev < 64) {
+        const int c = cached[dev].load(std::memory_order_relaxed);
+        if (c > 0) return c;
+    }
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+    if (dev >= 0 && dev < 64) cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
 
 // q8: the call came through an 8-bit entry point (then `scale` may be given and the descriptor must say SS_I8 or
 // SS_F8); the 16-bit entry points reject such descriptors.
@@ -205,6 +222,12 @@ using namespace ss;
 extern "C" int ss_debug_force_tile(int32_t id)
 {
     g_forced_tile.store(id < 0 ? -1 : id, std::memory_order_relaxed);
+    return SS_OK;
+}
+
+extern "C" int ss_debug_limit_blocks(int32_t n)
+{
+    g_block_limit.store(n < 0 ? 0 : n, std::memory_order_relaxed);
     return SS_OK;
 }
 

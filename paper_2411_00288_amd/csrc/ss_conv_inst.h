@@ -1,6 +1,7 @@
 // Instantiates the convolution kernels for one operand type and one operand form (2:4-sparse or dense), named by the
 // including file through SS_INST_NAME / SS_INST_DT / SS_INST_SPARSE / SS_INST_FUSED.
 #include "ss_conv_kernel.h"
+#include "ss_conv_stream.h"
 
 #define SS_CAT2(a, b) a##b
 #define SS_CAT(a, b) SS_CAT2(a, b)
@@ -9,6 +10,18 @@ namespace ss {
 
 int SS_CAT(conv_dispatch_, SS_INST_NAME)(const ss_weight_desc *desc, const ConvParams &p, hipStream_t s)
 {
+    if constexpr (!is_byte_type(SS_INST_DT)) {
+        if (stream_eligible(desc, p)) {
+            int ncu = compute_units();
+            if (ncu <= 0) return SS_ERR_HIP;
+            if (block_limit() > 0 && block_limit() < ncu) ncu = block_limit();
+            switch (forced_tile()) {
+                case 10: return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 4>(p, ncu, s);
+                case 11: return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 2>(p, ncu, s);
+                default: break;
+            }
+        }
+    }
     return pick_mode<SS_INST_DT, SS_INST_SPARSE>(desc, p, s);
 }
 

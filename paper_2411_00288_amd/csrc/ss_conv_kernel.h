@@ -189,7 +189,14 @@ struct ChunkShape {
     static constexpr int TAPS = KH * KW;
     static constexpr int KSTEPS = (MODE == MODE_TAPS) ? TAPS : (MODE == MODE_VEC8 ? 8 : (MODE == MODE_PW ? 4 : 2));   // 32-wide reduction steps per LDS chunk
     static constexpr int BK = KSTEPS * 32;
-    static constexpr int ROW = BK + 8;   // +16 bytes per pixel row: 16-byte LDS reads of consecutive pixels hit distinct banks
+    // Bank-conflict-free layout of a pixel row in LDS.  Default: +16 bytes per row, so that the 16-byte fragment reads
+    // of consecutive pixels hit distinct banks.  The 3x3 tap-transposing mode writes 16-byte vectors at a stride of 9
+    // vectors (one 8-channel unit) from four threads per pixel, which collides with any such padding; there the row
+    // is left unpadded (36 vectors) and the index of a 16-byte vector inside its row is XOR-ed with bits 2..3 of the
+    // pixel row (SWZ): the vector stays inside its aligned group of four, and both the transposed writes (4 pixel
+    // rows x 4 units per 16 lanes) and the fragment reads (16 consecutive pixel rows) cover all 64 banks exactly once.
+    static constexpr bool SWZ = MODE == MODE_TAPS && TAPS == 9;
+    static constexpr int ROW = SWZ ? BK : BK + 8;
     // LDS copies of the chunk: double-buffered, so that the next chunk is written while this one is
     // multiplied -- except for the large unfolded 3x3 chunk in the shallow variant, which is kept once
     // (more workgroups per compute unit then hide the store phase instead).
@@ -489,7 +496,8 @@ void conv_kernel(ConvParams p)
             int pr = pr0 + i * (ST / UNITS);
             if constexpr (MODE == MODE_TAPS) {
                 // [tap][8 channels] -> [channel][tap]: output element h = c*TAPS + tap, two per dword, four dwords per vector
-                u32x4 *dst = reinterpret_cast<u32x4 *>(Bs + pr * ROW + unit * (8 * TAPS));
+                u32x4 *rowp = reinterpret_cast<u32x4 *>(Bs + pr * ROW);
+                const int vec0 = unit * TAPS, swz = CS::SWZ ? (pr >> 2) & 3 : 0;     // first vector of the unit; the row's XOR key
 #pragma unroll
                 for (int v = 0; v < TAPS; v++) {
                     if (v < j * TAPS / n || v >= (j + 1) * TAPS / n) continue;
@@ -512,7 +520,7 @@ void conv_kernel(ConvParams p)
                             o[q] = __builtin_amdgcn_perm(p23, p01, 0x05040100u);
                         }
                         u32x4 w = {o[0], o[1], o[2], o[3]};
-                        dst[v] = w;
+                        rowp[(vec0 + v) ^ swz] = w;
                         continue;
                     }
 #pragma unroll
@@ -527,7 +535,7 @@ void conv_kernel(ConvParams p)
                         o[q] = __builtin_amdgcn_perm(sb, sa, sel);
                     }
                     u32x4 w = {o[0], o[1], o[2], o[3]};
-                    dst[v] = w;
+                    rowp[(vec0 + v) ^ swz] = w;
                 }
             } else {
                 if (i < j * ITEMS / n || i >= (j + 1) * ITEMS / n) continue;
@@ -570,6 +578,11 @@ void conv_kernel(ConvParams p)
             }
         }
     };
+
+    // This lane's two 16-byte vectors of a fragment inside the step's aligned group of four (in 16-bit units): lanes
+    // 0..31 take vectors 0, 1 and lanes 32..63 vectors 2, 3, XOR-ed with the pixel row's key in the swizzled layout.
+    const int frag_key = CS::SWZ ? (lane >> 2) & 3 : 0;
+    const int frag_lo = ((2 * (lane >> 5)) ^ frag_key) * 8, frag_hi = ((2 * (lane >> 5) + 1) ^ frag_key) * 8;
 
     Acc<DT> acc[TM][TN];
 #pragma unroll
@@ -649,9 +662,9 @@ void conv_kernel(ConvParams p)
             auto load_b = [&](B32 (&bf)[TN], int s) {
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++) {
-                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32 + 16 * (lane >> 5);
-                    bf[tn].lo = *reinterpret_cast<const u32x4 *>(src);
-                    bf[tn].hi = *reinterpret_cast<const u32x4 *>(src + 8);
+                    const uint16_t *src = cur + ((wn * TN + tn) * 32 + (lane & 31)) * ROW + s * 32;
+                    bf[tn].lo = *reinterpret_cast<const u32x4 *>(src + frag_lo);
+                    bf[tn].hi = *reinterpret_cast<const u32x4 *>(src + frag_hi);
                 }
             };
 #pragma unroll

@@ -55,6 +55,11 @@ constexpr int kMlpTiles = 2;      // 32x32 output tiles of the second layer per 
 
 // Test hook (ss_debug.h): the tile id forced by ss_debug_force_tile, or -1 when the library chooses.
 int forced_tile();
+// Test hook (ss_debug.h): upper bound on the workgroups of the resident-grid kernels, or 0 for none.
+int block_limit();
+
+// Compute units of the current device (cached per device), or -1 when the runtime cannot say.
+int compute_units();
 
 // One function per operand type and operand form, each defined in its own translation unit.  conv_dispatch_* picks
 // the staging mode and tile for the problem and launches; fused_dispatch_* does so for a k x k convolution followed by

@@ -31,3 +31,12 @@ def force_tile(ss):
         ss.ss_debug_force_tile(-1 if tid is None else int(tid))
     yield setter
     ss.ss_debug_force_tile(-1)
+
+
+@pytest.fixture
+def limit_blocks(ss):
+    """Caps the workgroups of the resident-grid kernels through the library's test hook; removed afterwards."""
+    def setter(n):
+        ss.ss_debug_limit_blocks(0 if n is None else int(n))
+    yield setter
+    ss.ss_debug_limit_blocks(0)
