@@ -175,8 +175,16 @@ int ss_dense_pack(const ss_weight_desc *desc, const void *W, const uint8_t *M, v
 int ss_weights_check(const ss_weight_desc *desc, const void *weights, int32_t sparse, void *stream);
 
 /*
- * Scratch the convolution needs for the given problem (fp32 partial sums when the reduction is
- * split across workgroups; 0 when it is not).  Same value for the sparse and the dense call.
+ * Scratch the convolution needs for the given problem on the current device: 0 for most problems.  Where the output
+ * has so few tiles that most compute units would idle (few output pixels and a long reduction: small-batch inference,
+ * the last stages of a network), the 16-bit convolutions split the reduction over several workgroups per output tile;
+ * the workspace then holds their fp32 partial sums and one ticket counter per tile.  The partial sums are added in a
+ * fixed order and rounded once, so the result does not depend on which workgroup finishes last.  Same value for the
+ * sparse and the dense call and for the calls with a residual; 0 for the 8-bit operand types.
+ *
+ * Contract of a non-empty workspace: 256-byte aligned; zero-filled by the caller once, before the first call that
+ * uses it (every call hands the ticket counters back at zero, so one clearing per allocation is enough, also under
+ * HIP-graph replay); not shared by calls that may run at the same time.
  */
 int ss_conv2d_workspace_bytes(const ss_weight_desc *desc, int32_t N, int32_t H, int32_t Wd,
                               int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
@@ -191,8 +199,8 @@ int ss_conv2d_workspace_bytes(const ss_weight_desc *desc, int32_t N, int32_t H, 
  *   bias      [cout] fp32, or NULL for no bias                              (read only)
  *   act       SS_ACT_NONE | SS_ACT_RELU | SS_ACT_GELU (z * Phi(z), exact normal CDF)
  *   y         [N][Ho][Wo][cout]  16-bit, desc->dtype                        (written)
- *   workspace ws_bytes >= ss_conv2d_workspace_bytes(...) bytes, 256-byte aligned; may be NULL
- *             when that size is 0.  Contents are scratch.
+ *   workspace ws_bytes >= ss_conv2d_workspace_bytes(...) bytes, see there; may be NULL when that size is 0
+ *             (SS_ERR_WORKSPACE when it is needed and missing or too small)
  * Asynchronous on `stream`; launch errors are returned as SS_ERR_HIP.
  */
 int ss_conv2d_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,

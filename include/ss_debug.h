@@ -21,6 +21,14 @@ extern "C" {
 int ss_debug_force_tile(int32_t id);
 
 /*
+ * Forces the number of workgroups that share one output tile of the 16-bit convolutions, each taking a share of the
+ * reduction (see ss_conv2d_workspace_bytes); the value is clamped to the number of reduction chunks, and layers whose
+ * staging mode does not split ignore it.  0 or a negative value returns the decision to the library.  The workspace
+ * query answers for the forced value, so query after forcing.  Process-wide, as above.  Always returns SS_OK.  [host]
+ */
+int ss_debug_force_split(int32_t n);
+
+/*
  * Caps the number of workgroups the resident-grid convolution kernels launch (they normally launch one per compute
  * unit and let each walk over several output tiles); 0 or a negative value removes the cap.  With a small cap a small
  * test problem exercises the tile-to-tile hand-over that otherwise only large problems reach.  Process-wide, as

@@ -25,7 +25,7 @@ EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_com
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
            "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd",
            "ss_weights_check"]
-DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks"]          # include/ss_debug.h: test hooks
+DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks", "ss_debug_force_split"]          # include/ss_debug.h: test hooks
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -74,6 +74,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_weights_check.argtypes = [dp, vp, i32, vp]
     lib.ss_debug_force_tile.argtypes = [i32]
     lib.ss_debug_limit_blocks.argtypes = [i32]
+    lib.ss_debug_force_split.argtypes = [i32]
     for name in EXPORTS[1:] + DEBUG_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -226,6 +227,11 @@ def ss_debug_limit_blocks(n: int) -> None:
     _lib.ss_debug_limit_blocks(int(n))
 
 
+def ss_debug_force_split(n: int) -> None:
+    """Test hook (include/ss_debug.h): force the number of workgroups per output tile; 0 = the library decides."""
+    _lib.ss_debug_force_split(int(n))
+
+
 def _nbytes(t) -> int:
     return 0 if t is None else t.numel() * t.element_size()
 
@@ -271,7 +277,7 @@ def _conv_args(what, desc, x, wbuf, bias, stride, pad, act, y, workspace, stream
     need = ss_conv2d_workspace_bytes(desc, N, H, W, stride, pad)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     if need > 0 and workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=x.device)      # the ticket counters must start at zero
         ws_bytes = need
     if residual is not None and (tuple(residual.shape) != shp or residual.dtype != x.dtype or not residual.is_contiguous()):
         raise SSError(SS_ERR_INVALID_ARG, f"{what}: residual must be contiguous {shp} {x.dtype}")
@@ -356,7 +362,7 @@ def _q8_args(what, desc, x, wbuf, scale, bias, stride, pad, act, y, workspace):
     need = ss_conv2d_workspace_bytes(desc, N, H, W, stride, pad)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     if need > 0 and workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=x.device)
         ws_bytes = need
     xtypes = (torch.int8,) if desc.dtype == SS_I8 else (torch.uint8, torch.float8_e4m3fn)
     args = (ctypes.byref(desc), _dev_ptr(x, "x", xtypes), N, H, W, _dev_ptr(wbuf, "weights"),

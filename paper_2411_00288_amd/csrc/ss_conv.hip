@@ -35,6 +35,16 @@ static std::atomic<int> g_forced_tile{-1};
 int forced_tile() { return g_forced_tile.load(std::memory_order_relaxed); }
 static std::atomic<int> g_block_limit{0};
 int block_limit() { return g_block_limit.load(std::memory_order_relaxed); }
+static std::atomic<int> g_forced_split{0};
+int forced_split() { return g_forced_split.load(std::memory_order_relaxed); }
+
+// Compute units the split heuristic plans for: those of the current device, or 256 (the MI355X count) when the runtime
+// has no device to ask, so that the size query still answers on a build host.
+static int planning_units()
+{
+    const int n = compute_units();
+    return n > 0 ? n : 256;
+}
 
 int compute_units()
 {
@@ -59,8 +69,6 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
                       int32_t act, void *y, void *workspace, size_t ws_bytes, void *stream, bool q8 = false,
                       const float *scale = nullptr)
 {
-    (void)workspace;
-    (void)ws_bytes;
     int st = check_desc(desc, SPARSE);
     if (st != SS_OK) return st;
     if (is_byte_type(desc->dtype) != q8) return q8 ? SS_ERR_INVALID_ARG : SS_ERR_UNSUPPORTED;
@@ -115,6 +123,24 @@ static int conv_entry(const ss_weight_desc *desc, const void *x, int32_t N, int3
     p.x_bytes = (unsigned)xbytes;
     p.a_bytes = (unsigned)((size_t)t.Mt * t.Ks * (SPARSE ? 1024 : 2048));
     p.meta_bytes = SPARSE ? (unsigned)((size_t)t.Mt * t.Kp * 256) : 4u;
+    // Split of the reduction over several workgroups per tile (16-bit operands, grids far below the chip's size): the
+    // partial sums and ticket counters live in the caller's workspace, which ss_conv2d_workspace_bytes sized from
+    // the same plan.
+    p.nsplit = 1;
+    p.plan_tile = -1;
+    if (!q8) {
+        const SplitPlan pl = plan_split(desc, P, t.Ks, planning_units(), forced_tile(), forced_split());
+        if (pl.nsplit > 1) {
+            if (!workspace || ws_bytes < pl.ctr_bytes + pl.part_bytes) return SS_ERR_WORKSPACE;
+            if (!aligned(workspace, 256)) return SS_ERR_INVALID_ARG;
+            p.nsplit = pl.nsplit;
+            p.plan_tile = pl.tile;
+            p.plan_bm = pl.bm;
+            p.plan_bn = pl.bn;
+            p.ws_ctr = static_cast<unsigned *>(workspace);
+            p.ws_part = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ctr_bytes);
+        }
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (desc->dtype) {
         case SS_I8: return SPARSE ? conv_dispatch_i8_sparse(desc, p, s) : conv_dispatch_i8_dense(desc, p, s);
@@ -225,6 +251,12 @@ extern "C" int ss_debug_force_tile(int32_t id)
     return SS_OK;
 }
 
+extern "C" int ss_debug_force_split(int32_t n)
+{
+    g_forced_split.store(n < 0 ? 0 : n, std::memory_order_relaxed);
+    return SS_OK;
+}
+
 extern "C" int ss_debug_limit_blocks(int32_t n)
 {
     g_block_limit.store(n < 0 ? 0 : n, std::memory_order_relaxed);
@@ -239,6 +271,12 @@ extern "C" int ss_conv2d_workspace_bytes(const ss_weight_desc *desc, int32_t N, 
     if (st != SS_OK) return st;
     if (N <= 0 || H <= 0 || Wd <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return SS_ERR_INVALID_ARG;
     *bytes = 0;
+    if (H + 2 * pad_h < desc->kh || Wd + 2 * pad_w < desc->kw) return SS_ERR_INVALID_ARG;
+    const long long Ho = (H + 2 * pad_h - desc->kh) / stride_h + 1, Wo = (Wd + 2 * pad_w - desc->kw) / stride_w + 1;
+    const long long P = (long long)N * Ho * Wo;
+    if (P >= (1ll << 31) - 512) return SS_ERR_UNSUPPORTED;
+    const SplitPlan pl = plan_split(desc, P, tile_dims(desc).Ks, planning_units(), forced_tile(), forced_split());
+    if (pl.nsplit > 1) *bytes = pl.ctr_bytes + pl.part_bytes;
     return SS_OK;
 }
 

@@ -11,15 +11,19 @@ namespace ss {
 int SS_CAT(conv_dispatch_, SS_INST_NAME)(const ss_weight_desc *desc, const ConvParams &p, hipStream_t s)
 {
     if constexpr (!is_byte_type(SS_INST_DT)) {
-        if (stream_eligible(desc, p)) {
+        if (p.nsplit <= 1 && stream_eligible(desc, p)) {
             int ncu = compute_units();
             if (ncu <= 0) return SS_ERR_HIP;
             if (block_limit() > 0 && block_limit() < ncu) ncu = block_limit();
-            switch (forced_tile()) {
-                case 10: return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 4>(p, ncu, s);
-                case 11: return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 2>(p, ncu, s);
-                default: break;
-            }
+            const int forced = forced_tile();
+            // The resident-grid kernel pays where every compute unit gets at least two of its 256 x 128 tiles (measured:
+            // 16-20 % faster than the one-tile kernels at three tiles per compute unit, slower at one) and the 256-row
+            // tile is mostly filled.
+            const long long tiles = (long long)((p.Cout + 255) / 256) * (((long long)p.P + 127) / 128);
+            const bool pays = p.Cout % 256 == 0 || p.Cout % 256 >= 192;
+            if (forced == 10 || (forced < 0 && pays && tiles >= 2ll * ncu))
+                return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 4>(p, ncu, s);
+            if (forced == 11) return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 2>(p, ncu, s);
         }
     }
     return pick_mode<SS_INST_DT, SS_INST_SPARSE>(desc, p, s);

@@ -295,7 +295,16 @@ void conv_kernel(ConvParams p)
     // that an XCD works on a contiguous run of tiles: both row tiles of a pixel tile, and pixel tiles
     // that share halo rows, then hit the same L2.
     const int nb = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int lid = xcd * (nb >> 3) + min(xcd, nb & 7) + slot;
+    const int lidx = xcd * (nb >> 3) + min(xcd, nb & 7) + slot;
+    // Split reduction (p.nsplit > 1): consecutive workgroups share an output tile and each takes a contiguous share
+    // of the reduction chunks; their fp32 partial sums meet in the workspace (see the epilogue).
+    constexpr bool CAN_SPLIT = !FUSE && !is_byte_type(DT);
+    const int nsplit = CAN_SPLIT ? p.nsplit : 1;
+    const int split = nsplit > 1 ? lidx % nsplit : 0;
+    const int lid = nsplit > 1 ? lidx / nsplit : lidx;
+    const int nchunks_all = (p.Ks + ChunkShape<MODE, KH, KW, DEEP>::KSTEPS - 1) / ChunkShape<MODE, KH, KW, DEEP>::KSTEPS;
+    const int c_first = split * nchunks_all / nsplit;                  // this workgroup's chunks: [c_first, c_first + nchunks)
+    const int nchunks = (split + 1) * nchunks_all / nsplit - c_first;
     const int tile_n = fast_div(lid, p.tm_mul, p.tm_sh);
     const int tile_m = lid - tile_n * p.tiles_m;
     const int m0 = tile_m * BM;
@@ -364,7 +373,7 @@ void conv_kernel(ConvParams p)
     }
 
     // MODE_VEC: position of this thread's 8-element run in the (tap, channel) space
-    int vk = unit * 8, vc = 0, vr = 0, vt = 0;
+    int vk = unit * 8 + c_first * ChunkShape<MODE, KH, KW, DEEP>::BK, vc = 0, vr = 0, vt = 0;
     if constexpr (is_vec(MODE)) {
         int tap = vk / p.Cin;
         vc = vk - tap * p.Cin;
@@ -402,8 +411,9 @@ void conv_kernel(ConvParams p)
     uint2 stage_g4_[NSET][MODE == MODE_GATHER4 ? ITEMS : 1];
     u32x4 stage_t_[NSET][MODE == MODE_TAPS ? ITEMS : 1][MODE == MODE_TAPS ? TAPS : 1];
 
-    auto stage_load = [&](int ci, int set = 0) {      // set: compile time at every call site
+    auto stage_load = [&](int ci_rel, int set = 0) {      // set: compile time at every call site; chunk relative to c_first
         if (!stager) return;
+        const int ci = ci_rel + c_first;
         auto &stage_v = stage_v_[set];
         auto &stage_g = stage_g_[set];
         auto &stage_t = stage_t_[set];
@@ -563,8 +573,9 @@ void conv_kernel(ConvParams p)
         a_voff[tm] = (unsigned)((mt * p.Ks * (SPARSE ? 1 : 2)) * 64 + lane) * 16u;
         m_voff[tm] = (unsigned)(mt * p.Kp * 64 + lane) * 4u;
     }
-    auto load_a = [&](AStep<SPARSE, TM> &a, int ks_raw) {
-        const int ks = min(ks_raw, p.Ks - 1);
+    const int ks_first = c_first * KSTEPS;
+    auto load_a = [&](AStep<SPARSE, TM> &a, int ks_rel) {       // step relative to this workgroup's first
+        const int ks = min(ks_rel + ks_first, p.Ks - 1);
 #pragma unroll
         for (int tm = 0; tm < TM; tm++) {
             if constexpr (SPARSE) {
@@ -593,7 +604,6 @@ void conv_kernel(ConvParams p)
             for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0;
 
     // ------------------------------------------------------------------ main loop (double-buffered LDS, ring of weight steps)
-    const int nchunks = (p.Ks + KSTEPS - 1) / KSTEPS;
     AStep<SPARSE, TM> a[RING];
     if constexpr (SPEC) {
         if (producer) {
@@ -682,7 +692,7 @@ void conv_kernel(ConvParams p)
                 // cheaper than a branch, which would force copies of every accumulator)
                 const AStep<SPARSE, TM> &as = a[g % RING];
                 // the 16-bit instruction reads index bits [15:0]; the 8-bit one the whole word
-                const int idx_shift = Q8 ? 0 : (min(ci * KSTEPS + s, p.Ks - 1) & 1) * 16;
+                const int idx_shift = Q8 ? 0 : (min(ks_first + ci * KSTEPS + s, p.Ks - 1) & 1) * 16;
 #pragma unroll
                 for (int tm = 0; tm < TM; tm++)
 #pragma unroll
@@ -734,6 +744,58 @@ void conv_kernel(ConvParams p)
     // CDF, written with erfc so that the lower tail keeps its relative accuracy
     auto relu_or_id = [&](float v) { return v < relu_floor ? 0.f : v; };
     auto gelu = [](float v) { return gelu_erfc(v); };
+    if constexpr (CAN_SPLIT) {
+        if (nsplit > 1) {
+            // Every workgroup of the tile leaves its partial sums in the workspace, in register order (one 16-byte
+            // vector per thread and accumulator quad: fully coalesced), and takes a ticket.  The last one to arrive adds
+            // the partials in the order of the splits -- so the result does not depend on who arrived last --, hands the
+            // ticket counter back at zero for the next launch, and runs the usual tail; the others are done.
+            float *part = p.ws_part + (size_t)lid * nsplit * (BM * BN);
+            const int mtid = etid;                      // (multiplying threads are 0 .. NMATH-1)
+            if (!producer) {
+                float *mine = part + (size_t)split * (BM * BN);
+#pragma unroll
+                for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                        for (int q = 0; q < 4; q++)
+                            *reinterpret_cast<float4 *>(mine + ((size_t)((tm * TN + tn) * 4 + q) * NMATH + mtid) * 4) =
+                                make_float4(acc[tm][tn][4 * q + 0], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2], acc[tm][tn][4 * q + 3]);
+            }
+            __threadfence();                            // the partial sums are visible device-wide before the ticket is taken
+            __syncthreads();
+            unsigned *ticket_s = reinterpret_cast<unsigned *>(smem);      // (the staging buffers are free)
+            if (etid == 0) *ticket_s = atomicAdd(p.ws_ctr + lid, 1u);
+            __syncthreads();
+            const unsigned ticket = *ticket_s;
+            if (ticket != (unsigned)(nsplit - 1)) return;                 // (uniform)
+            __threadfence();                            // the other workgroups' partial sums are visible here
+            if (etid == 0) p.ws_ctr[lid] = 0u;
+            if (!producer) {
+#pragma unroll
+                for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                        for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0.f;
+                for (int j = 0; j < nsplit; j++) {
+                    const float *src = part + (size_t)j * (BM * BN);
+#pragma unroll
+                    for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+                        for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                            for (int q = 0; q < 4; q++) {
+                                const float4 v = *reinterpret_cast<const float4 *>(src + ((size_t)((tm * TN + tn) * 4 + q) * NMATH + mtid) * 4);
+                                acc[tm][tn][4 * q + 0] += v.x; acc[tm][tn][4 * q + 1] += v.y;
+                                acc[tm][tn][4 * q + 2] += v.z; acc[tm][tn][4 * q + 3] += v.w;
+                            }
+                }
+            }
+            __syncthreads();                            // the ticket word's LDS is about to hold the output tile
+        }
+    }
     if (!with_res) {
         constexpr int CROW = BM + 4;     // halfs per pixel row in LDS (+8 bytes: the 8-byte writes of 32 consecutive pixels spread over all banks)
         uint16_t *Cs = smem;             // the staging buffers are free: the loop ended with a barrier (every wave, producers included, ran the same number)
@@ -1207,6 +1269,12 @@ static int launch(const ConvParams &p0, hipStream_t s)
     fast_div_setup((unsigned)p.tiles_m, &p.tm_mul, &p.tm_sh);
     long long tiles_n = ((long long)p.P + BN - 1) / BN;
     long long blocks = (long long)p.tiles_m * tiles_n;
+    if (FUSE || is_byte_type(DT) || p.nsplit < 1) p.nsplit = 1;
+    if (p.nsplit > 1) {
+        // the entry point planned the split for this very tile shape (plan_split) and sized the workspace for it
+        if (p.ws_part == nullptr || p.ws_ctr == nullptr || p.plan_bm != BM || p.plan_bn != BN) return SS_ERR_WORKSPACE;
+        blocks *= p.nsplit;
+    }
     if (blocks <= 0 || blocks > 0x7FFFFFFFll) return SS_ERR_UNSUPPORTED;
     auto kern = conv_kernel<DT, SPARSE, WAVES_M, WAVES_N, TM, TN, MODE, KH, KW, DEEP, SPEC, FUSE>;
     if (smem_res > 64 * 1024) {
@@ -1225,11 +1293,6 @@ static int launch(const ConvParams &p0, hipStream_t s)
     }
     kern<<<dim3((unsigned)blocks), dim3((WAVES_M * WAVES_N + (SPEC ? 4 : 0)) * 64), smem, s>>>(p);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
-}
-
-static inline long long n_blocks(const ConvParams &p, int bm, int bn)
-{
-    return (long long)((p.Cout + bm - 1) / bm) * (((long long)p.P + bn - 1) / bn);
 }
 
 // Tile shapes (WAVES_M x WAVES_N multiplying waves, each TM x TN tiles of 32x32):
@@ -1265,28 +1328,10 @@ static int launch_tile(int id, const ConvParams &p, hipStream_t s)
     return SS_ERR_INVALID_ARG;
 }
 
-// Tile id for a problem.  Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes, 256 compute
-// units).  pointwise: 1x1 staging; bigchunk: staging in chunks of 256+ reduction indices (3x3 tap transpose, long
-// channels-last reductions).
-static inline int choose_tile(const ConvParams &p, bool pointwise, bool bigchunk)
-{
-    if (p.Cout <= 64) {
-        const bool deep = n_blocks(p, 64, 64) <= 1024 || (pointwise && p.K >= 256);
-        return deep ? 1 : 0;
-    }
-    // Grids of at most one workgroup per compute unit: nothing else hides a wave's stalls, so separate producer
-    // waves pay.  Larger grids do better with two four-wave workgroups per compute unit.
-    const long long b128 = n_blocks(p, 128, 64), b256 = n_blocks(p, 256, 64);
-    if (p.Cout > 128 && b256 > 128 && b256 <= 256) return 5;
-    if (b128 <= 256) return 4;
-    if (p.Cout >= 512 && p.K >= 512) return 3;
-    if (bigchunk && p.Cout >= 256 && b256 >= 512) return 3;
-    return 2;
-}
-
 template <int DT, bool SPARSE, int MODE, int KH, int KW>
 static int pick_tile(const ConvParams &p, hipStream_t s)
 {
+    if (p.nsplit > 1) return launch_tile<DT, SPARSE, MODE, KH, KW>(p.plan_tile, p, s);     // planned by the entry point
     const int forced = forced_tile();                  // test hook (ss_debug.h): a tile shape by id, or -1
     if (forced >= 0) {
         int st = launch_tile<DT, SPARSE, MODE, KH, KW>(forced, p, s);

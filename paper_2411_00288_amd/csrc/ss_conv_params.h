@@ -27,6 +27,11 @@ struct ConvParams {
     uint16_t *y2;             // [P][Cout2]
     int Cout2, Ks2, Kp2, Mt2, act2;
     unsigned a2_bytes, meta2_bytes;
+    // split reduction: workgroups per output tile (1 = none), fp32 partial sums [tile][split][BM*BN] and one ticket
+    // counter per tile, both in the caller's workspace
+    int nsplit, plan_tile, plan_bm, plan_bn;      // plan_*: the tile the split was planned (and the workspace sized) for
+    float *ws_part;
+    unsigned *ws_ctr;
 };
 
 // floor(n / d) for 0 <= n < 2^31 as (n * mul) >> sh with s = ceil(log2 d), sh = 31 + s, mul = ceil(2^sh / d):
@@ -53,10 +58,80 @@ struct MlpParams {
 constexpr int kMlpKs1 = 4;        // first reduction: at most 128 input channels
 constexpr int kMlpTiles = 2;      // 32x32 output tiles of the second layer per wave: at most 128 output channels x 64 pixels over 4 waves
 
+static inline long long n_blocks(const ConvParams &p, int bm, int bn)
+{
+    return (long long)((p.Cout + bm - 1) / bm) * (((long long)p.P + bn - 1) / bn);
+}
+
+
+// Tile id for a problem.  Measured on MI355X (tile sweep over the ResNet-50 / ConvNeXt-T layer shapes, 256 compute
+// units).  pointwise: 1x1 staging; bigchunk: staging in chunks of 256+ reduction indices (3x3 tap transpose, long
+// channels-last reductions).
+static inline int choose_tile(const ConvParams &p, bool pointwise, bool bigchunk)
+{
+    if (p.Cout <= 64) {
+        const bool deep = n_blocks(p, 64, 64) <= 1024 || (pointwise && p.K >= 256);
+        return deep ? 1 : 0;
+    }
+    // Grids of at most one workgroup per compute unit: nothing else hides a wave's stalls, so separate producer
+    // waves pay.  Larger grids do better with two four-wave workgroups per compute unit.
+    const long long b128 = n_blocks(p, 128, 64), b256 = n_blocks(p, 256, 64);
+    if (p.Cout > 128 && b256 > 128 && b256 <= 256) return 5;
+    if (b128 <= 256) return 4;
+    if (p.Cout >= 512 && p.K >= 512) return 3;
+    if (bigchunk && p.Cout >= 256 && b256 >= 512) return 3;
+    return 2;
+}
+
+
+// Split of a convolution's reduction over several workgroups per output tile (for grids that leave most compute
+// units idle: few output pixels, long reductions -- small-batch inference and the last stages of a network).
+struct SplitPlan {
+    int tile, bm, bn, nsplit;        // tile id and shape; workgroups per output tile (1 = no split, nothing else is used)
+    long long tiles;
+    size_t ctr_bytes, part_bytes;    // workspace: ticket counters, then fp32 partial sums [tile][split][bm * bn]
+};
+// Decides tile and split for a 16-bit problem.  Only the two staging modes of the networks' own layers split (1x1
+// kernels with more than two 32-wide steps; 3x3 kernels in the channel-slowest flattening with cin % 32 == 0).
+// forced_tile / forced_split: test hooks (negative / zero: the library decides).  A split happens by itself when the
+// grid would leave at least half of the compute units idle and every share keeps at least two chunks.
+inline SplitPlan plan_split(const ss_weight_desc *d, long long P, int Ks, int ncu, int forced_tile, int forced_split)
+{
+    SplitPlan pl{};
+    pl.nsplit = 1;
+    if (is_byte_type(d->dtype)) return pl;
+    const bool pw = d->kh * d->kw == 1 && d->cin % 8 == 0 && Ks > 2;
+    const bool taps = d->korder == SS_K_CRS && d->kh == 3 && d->kw == 3 && d->cin % 32 == 0;
+    if (!pw && !taps) return pl;
+    const int ksteps = taps ? 9 : 4;
+    ConvParams q{};
+    q.Cout = d->cout; q.P = (int)P; q.K = d->cin * d->kh * d->kw;
+    pl.tile = (forced_tile >= 0 && forced_tile <= 5) ? forced_tile : choose_tile(q, pw, taps);
+    pl.bm = pl.tile <= 1 ? 64 : ((pl.tile == 2 || pl.tile == 4) ? 128 : 256);
+    pl.bn = 64;
+    pl.tiles = n_blocks(q, pl.bm, pl.bn);
+    const int nchunks = (Ks + ksteps - 1) / ksteps;
+    int n = 1;
+    if (forced_split > 0) n = forced_split;
+    else if (forced_tile < 0 && pl.tiles * 2 <= ncu && nchunks >= 4) {
+        n = (int)(ncu / pl.tiles);
+        if (n > nchunks / 2) n = nchunks / 2;
+        if (n > 8) n = 8;
+    }
+    if (n > nchunks) n = nchunks;
+    if (n < 1) n = 1;
+    pl.nsplit = n;
+    pl.ctr_bytes = (size_t)((pl.tiles * 4 + 255) / 256 * 256);
+    pl.part_bytes = (size_t)pl.tiles * n * pl.bm * pl.bn * 4;
+    return pl;
+}
+
 // Test hook (ss_debug.h): the tile id forced by ss_debug_force_tile, or -1 when the library chooses.
 int forced_tile();
 // Test hook (ss_debug.h): upper bound on the workgroups of the resident-grid kernels, or 0 for none.
 int block_limit();
+// Test hook (ss_debug.h): workgroups per output tile forced by ss_debug_force_split, or 0 when the library decides.
+int forced_split();
 
 // Compute units of the current device (cached per device), or -1 when the runtime cannot say.
 int compute_units();

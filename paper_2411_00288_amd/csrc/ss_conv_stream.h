@@ -26,7 +26,7 @@
 namespace ss {
 
 #ifndef SS_STREAM_PACE
-#define SS_STREAM_PACE 1      // s_sleep argument (units of 64 clocks) between a producer thread's load / LDS-write pairs
+#define SS_STREAM_PACE 0      // s_sleep argument (units of 64 clocks) between a producer thread's load / LDS-write pairs; 0 = none
 #endif
 
 // Workgroup barrier that orders LDS traffic only: the waves' outstanding global loads (weight ring, staging loads)
@@ -160,10 +160,10 @@ void conv3x3_stream_kernel(ConvParams p, int tiles_n, int slots_n)
 #pragma unroll
                 for (int v = 0; v < TAPS; v++) store_one(buf, set, i, v);
         };
-        // Steady state: the loads of one chunk and the LDS writes of the previous one, interleaved and paced.  The
-        // vector-memory path and the LDS write port serve a compute unit's requests in order: a burst of 18 loads (or
-        // writes) per thread would sit in front of the multiplying waves' weight loads (fragment reads) for a
-        // thousand clocks per chunk, far longer than their prefetch distance covers.
+        // Steady state: the loads of one chunk and the LDS writes of the previous one, interleaved, so that neither the
+        // vector-memory path nor the LDS write port sees a burst of 18 requests per thread in front of the multiplying
+        // waves' weight loads and fragment reads.  (Pacing the pairs with s_sleep was measured too: no gain at 64
+        // clocks per pair, a loss from 128 on.)
         auto load_store = [&](int lset, uint16_t *buf, int sset) {
 #pragma unroll
             for (int i = 0; i < ITEMS; i++)
@@ -171,7 +171,7 @@ void conv3x3_stream_kernel(ConvParams p, int tiles_n, int slots_n)
                 for (int v = 0; v < TAPS; v++) {
                     load_one(lset, i, v);
                     store_one(buf, sset, i, v);
-                    __builtin_amdgcn_s_sleep(SS_STREAM_PACE);
+                    if (SS_STREAM_PACE > 0) __builtin_amdgcn_s_sleep(SS_STREAM_PACE);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             advance();

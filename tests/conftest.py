@@ -40,3 +40,12 @@ def limit_blocks(ss):
         ss.ss_debug_limit_blocks(0 if n is None else int(n))
     yield setter
     ss.ss_debug_limit_blocks(0)
+
+
+@pytest.fixture
+def force_split(ss):
+    """Forces the number of workgroups per output tile (split reduction) through the library's test hook."""
+    def setter(n):
+        ss.ss_debug_force_split(0 if n is None else int(n))
+    yield setter
+    ss.ss_debug_force_split(0)
