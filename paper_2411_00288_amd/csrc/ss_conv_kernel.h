@@ -40,6 +40,7 @@ typedef _Float16 f16x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -296,12 +297,15 @@ void conv_kernel(ConvParams p)
     // that share halo rows, then hit the same L2.
     const int nb = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int lidx = xcd * (nb >> 3) + min(xcd, nb & 7) + slot;
-    // Split reduction (p.nsplit > 1): consecutive workgroups share an output tile and each takes a contiguous share
-    // of the reduction chunks; their fp32 partial sums meet in the workspace (see the epilogue).
+    // Split reduction (p.nsplit > 1): nsplit workgroups share an output tile and each takes a contiguous share of the
+    // reduction chunks; their fp32 partial sums meet in the workspace (see the epilogue).
     constexpr bool CAN_SPLIT = !FUSE && !is_byte_type(DT);
     const int nsplit = CAN_SPLIT ? p.nsplit : 1;
-    const int split = nsplit > 1 ? lidx % nsplit : 0;
-    const int lid = nsplit > 1 ? lidx / nsplit : lidx;
+    // (split-major numbering: neighbouring workgroups, which land on the same XCD, work on neighbouring tiles with the
+    // same share of the reduction and so share that share's weights in their L2)
+    const int ntiles = nsplit > 1 ? nb / nsplit : nb;
+    const int split = nsplit > 1 ? lidx / ntiles : 0;
+    const int lid = nsplit > 1 ? lidx - split * ntiles : lidx;
     const int nchunks_all = (p.Ks + ChunkShape<MODE, KH, KW, DEEP>::KSTEPS - 1) / ChunkShape<MODE, KH, KW, DEEP>::KSTEPS;
     const int c_first = split * nchunks_all / nsplit;                  // this workgroup's chunks: [c_first, c_first + nchunks)
     const int nchunks = (split + 1) * nchunks_all / nsplit - c_first;
@@ -750,28 +754,36 @@ void conv_kernel(ConvParams p)
             // vector per thread and accumulator quad: fully coalesced), and takes a ticket.  The last one to arrive adds
             // the partials in the order of the splits -- so the result does not depend on who arrived last --, hands the
             // ticket counter back at zero for the next launch, and runs the usual tail; the others are done.
-            float *part = p.ws_part + (size_t)lid * nsplit * (BM * BN);
+            // The workgroups of a tile may run on different XCDs, whose L2 caches are not coherent with each other.  The
+            // partial sums are therefore stored and loaded with the device-scope cache policy (sc1: written through to,
+            // and read from, the level all XCDs share -- what a relaxed device-scope atomic store / load compiles to),
+            // every wave waits for the acknowledgement of its stores before the workgroup takes its ticket, and the
+            // ticket is a device-scope atomic.  Device-scope fences would do as well, but they write back (release) and
+            // invalidate (acquire) the XCD's whole L2 under the workgroups still in their main loops: measured at
+            // 3 us per doubling of the split with the release fence alone, 4-8 us per workgroup with both.
+            constexpr int kDeviceScope = 16;            // cache-policy bit sc1 of the buffer instructions
+            const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(p.ws_part + (size_t)lid * nsplit * (BM * BN), 0,
+                                                                               nsplit * (BM * BN) * 4, kRsrcFlags);
             const int mtid = etid;                      // (multiplying threads are 0 .. NMATH-1)
             if (!producer) {
-                float *mine = part + (size_t)split * (BM * BN);
 #pragma unroll
                 for (int tm = 0; tm < TM; tm++)
 #pragma unroll
                     for (int tn = 0; tn < TN; tn++)
 #pragma unroll
-                        for (int q = 0; q < 4; q++)
-                            *reinterpret_cast<float4 *>(mine + ((size_t)((tm * TN + tn) * 4 + q) * NMATH + mtid) * 4) =
-                                make_float4(acc[tm][tn][4 * q + 0], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2], acc[tm][tn][4 * q + 3]);
+                        for (int q = 0; q < 4; q++) {
+                            const f32x4 fw = {(float)acc[tm][tn][4 * q + 0], (float)acc[tm][tn][4 * q + 1], (float)acc[tm][tn][4 * q + 2], (float)acc[tm][tn][4 * q + 3]};
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, fw), rp, (((tm * TN + tn) * 4 + q) * NMATH + mtid) * 16, split * (BM * BN * 4), kDeviceScope);
+                        }
             }
-            __threadfence();                            // the partial sums are visible device-wide before the ticket is taken
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's partial sums have been acknowledged
             __syncthreads();
             unsigned *ticket_s = reinterpret_cast<unsigned *>(smem);      // (the staging buffers are free)
-            if (etid == 0) *ticket_s = atomicAdd(p.ws_ctr + lid, 1u);
+            if (etid == 0) *ticket_s = __hip_atomic_fetch_add(p.ws_ctr + lid, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
             const unsigned ticket = *ticket_s;
             if (ticket != (unsigned)(nsplit - 1)) return;                 // (uniform)
-            __threadfence();                            // the other workgroups' partial sums are visible here
-            if (etid == 0) p.ws_ctr[lid] = 0u;
+            if (etid == 0) __hip_atomic_store(p.ws_ctr + lid, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (!producer) {
 #pragma unroll
                 for (int tm = 0; tm < TM; tm++)
@@ -780,16 +792,16 @@ void conv_kernel(ConvParams p)
 #pragma unroll
                         for (int v = 0; v < 16; v++) acc[tm][tn][v] = 0.f;
                 for (int j = 0; j < nsplit; j++) {
-                    const float *src = part + (size_t)j * (BM * BN);
 #pragma unroll
                     for (int tm = 0; tm < TM; tm++)
 #pragma unroll
                         for (int tn = 0; tn < TN; tn++)
 #pragma unroll
                             for (int q = 0; q < 4; q++) {
-                                const float4 v = *reinterpret_cast<const float4 *>(src + ((size_t)((tm * TN + tn) * 4 + q) * NMATH + mtid) * 4);
-                                acc[tm][tn][4 * q + 0] += v.x; acc[tm][tn][4 * q + 1] += v.y;
-                                acc[tm][tn][4 * q + 2] += v.z; acc[tm][tn][4 * q + 3] += v.w;
+                                // (the whole vector is reinterpreted at once: a bit cast of a single vector element reads element 0)
+                                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rp, (((tm * TN + tn) * 4 + q) * NMATH + mtid) * 16, j * (BM * BN * 4), kDeviceScope));
+                                acc[tm][tn][4 * q + 0] += v[0]; acc[tm][tn][4 * q + 1] += v[1];
+                                acc[tm][tn][4 * q + 2] += v[2]; acc[tm][tn][4 * q + 3] += v[3];
                             }
                 }
             }

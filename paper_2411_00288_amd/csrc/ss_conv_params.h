@@ -94,7 +94,7 @@ struct SplitPlan {
 // Decides tile and split for a 16-bit problem.  Only the two staging modes of the networks' own layers split (1x1
 // kernels with more than two 32-wide steps; 3x3 kernels in the channel-slowest flattening with cin % 32 == 0).
 // forced_tile / forced_split: test hooks (negative / zero: the library decides).  A split happens by itself when the
-// grid would leave at least half of the compute units idle and every share keeps at least two chunks.
+// grid would leave at least half of the compute units idle and the reduction is long enough to pay for the hand-over.
 inline SplitPlan plan_split(const ss_weight_desc *d, long long P, int Ks, int ncu, int forced_tile, int forced_split)
 {
     SplitPlan pl{};
@@ -113,10 +113,16 @@ inline SplitPlan plan_split(const ss_weight_desc *d, long long P, int Ks, int nc
     const int nchunks = (Ks + ksteps - 1) / ksteps;
     int n = 1;
     if (forced_split > 0) n = forced_split;
-    else if (forced_tile < 0 && pl.tiles * 2 <= ncu && nchunks >= 4) {
+    else if (forced_tile < 0 && pl.tiles * 2 <= ncu) {
+        // Measured on MI355X: handing the partial sums over costs about as much as four 3x3 chunks (sixteen of the
+        // shorter 1x1 chunks), so a share keeps at least that many.  (512 -> 512 3x3 at 7x7: batch 1, 4 tiles, 14.5 us
+        // whole, 9.6 us in four shares; batch 8, 28 tiles, 14.8 -> 11.7 us; reductions of 2304 and the 1x1 layers up
+        // to 2048 channels gained nothing and stay whole.)
+        const int per_share = taps ? 4 : 16;
         n = (int)(ncu / pl.tiles);
-        if (n > nchunks / 2) n = nchunks / 2;
+        if (n > nchunks / per_share) n = nchunks / per_share;
         if (n > 8) n = 8;
+        if (nchunks < 3 * per_share) n = 1;
     }
     if (n > nchunks) n = nchunks;
     if (n < 1) n = 1;
