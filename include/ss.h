@@ -209,6 +209,22 @@ int ss_conv2d_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t 
                   void *y, void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * ss_conv2d_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP-graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace pair, same kernels, same
+ * result bits.  The scratch of a split reduction lives in a device array inside the library's code object instead:
+ * 16 MiB + 64 KiB per GPU the library runs on, held until the process ends; that is the largest workspace the library
+ * plans by itself (ss_conv2d_workspace_bytes never reports more unless a test hook forces a split), and a problem that
+ * would need more is rejected with SS_ERR_WORKSPACE.  The call allocates and frees nothing.  All calls on one GPU
+ * share the array: it starts out zero, every call hands its ticket counters back at zero, and calls that may run at
+ * the same time on one GPU (different streams, different threads) race on it -- serialise them or use ss_conv2d_fwd
+ * with workspaces of their own.
+ */
+int ss_conv2d_fwd_static_ws(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                            const void *packed, const float *bias,
+                            int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act,
+                            void *y, void *stream);
+
+/*
  * The same-design dense twin: identical tiling, staging and epilogue, with the dense MFMA
  * instruction on the operand built by ss_dense_pack.  Denominator of the speed-up metric, and
  * the path for layers that stay dense.

@@ -24,7 +24,7 @@ EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_com
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
            "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd",
-           "ss_weights_check"]
+           "ss_weights_check", "ss_conv2d_fwd_static_ws"]
 DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks", "ss_debug_force_split"]          # include/ss_debug.h: test hooks
 
 
@@ -72,6 +72,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_conv2d_pw_fused_fwd.argtypes = fused_args
     lib.ss_conv2d_pw_fused_dense_fwd.argtypes = fused_args
     lib.ss_weights_check.argtypes = [dp, vp, i32, vp]
+    lib.ss_conv2d_fwd_static_ws.argtypes = conv_args[:13] + [vp]            # no workspace pair
     lib.ss_debug_force_tile.argtypes = [i32]
     lib.ss_debug_limit_blocks.argtypes = [i32]
     lib.ss_debug_force_split.argtypes = [i32]
@@ -322,6 +323,30 @@ def ss_conv2d_fwd(desc, x, packed, bias=None, stride=(1, 1), pad=(0, 0), act=SS_
                   stream=None) -> torch.Tensor:
     """2:4-sparse convolution: x NHWC [N,H,W,cin] -> y NHWC [N,Ho,Wo,cout] (same 16-bit dtype)."""
     return _conv(_lib.ss_conv2d_fwd, "ss_conv2d_fwd", desc, x, packed, bias, stride, pad, act, y, workspace, stream)
+
+
+def ss_conv2d_fwd_static_ws(desc, x, packed, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,
+                            stream=None) -> torch.Tensor:
+    """ss_conv2d_fwd without a workspace argument: a split reduction's scratch is the library's own device array.
+    `y` should be passed by callers that must not allocate (it is allocated here otherwise)."""
+    what = "ss_conv2d_fwd_static_ws"
+    if x is None or x.dim() != 4 or x.shape[3] != desc.cin:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: x must be NHWC with cin channels")
+    N, H, W, _ = x.shape
+    _check_operands(what, desc, packed, bias, True)
+    shp = out_shape(desc, N, H, W, stride, pad)
+    if shp[1] <= 0 or shp[2] <= 0:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: empty output")
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    elif tuple(y.shape) != shp or y.dtype != x.dtype:
+        raise SSError(SS_ERR_INVALID_ARG, f"{what}: y must be {shp} {x.dtype}")
+    st = _lib.ss_conv2d_fwd_static_ws(ctypes.byref(desc), _dev_ptr(x, "x", (torch_dtype(desc.dtype),)), N, H, W,
+                                      _dev_ptr(packed, "weights"), _dev_ptr(bias, "bias", (torch.float32,), allow_none=True),
+                                      stride[0], stride[1], pad[0], pad[1], act, _dev_ptr(y, "y"), _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, what)
+    return y
 
 
 def ss_conv2d_dense_fwd(desc, x, dense, bias=None, stride=(1, 1), pad=(0, 0), act=SS_ACT_NONE, y=None,

@@ -288,6 +288,46 @@ extern "C" int ss_conv2d_fwd(const ss_weight_desc *desc, const void *x, int32_t 
                             workspace, ws_bytes, stream);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Entry point for callers that cannot provide a workspace: the split reduction's scratch lives in a device array
+// that is part of the library's code object (one copy per GPU, held until the process ends).
+// ---------------------------------------------------------------------------------------------
+namespace {
+// Largest workspace the library plans by itself: a split happens only while tiles x shares <= compute units (256),
+// each share holds at most a 256 x 64 tile of fp32 partial sums (64 KiB), plus the ticket counters.
+constexpr size_t kStaticWsBytes = ((size_t)16 << 20) + ((size_t)64 << 10);
+__device__ __align__(256) unsigned char scratch[kStaticWsBytes];      // zero at load; every call hands its counters back at zero
+
+// Device address of `scratch` on the current device (each GPU holds its own copy at its own address), looked up once
+// per device.  In host code the array's name is only a handle for this lookup, never an address.
+void *static_workspace()
+{
+    static std::atomic<void *> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    if (dev >= 0 && dev < 64) {
+        void *p = cached[dev].load(std::memory_order_acquire);
+        if (p) return p;
+    }
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+    if (dev >= 0 && dev < 64) cached[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+}  // namespace
+
+extern "C" int ss_conv2d_fwd_static_ws(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
+                                       const void *packed, const float *bias, int32_t stride_h, int32_t stride_w,
+                                       int32_t pad_h, int32_t pad_w, int32_t act, void *y, void *stream)
+{
+    void *ws = static_workspace();
+    if (!ws) return SS_ERR_HIP;
+    // (a problem whose plan needs more than the array holds -- only a forced split can -- is rejected with
+    // SS_ERR_WORKSPACE by the size check of the common entry)
+    return conv_entry<true>(desc, x, N, H, Wd, packed, bias, nullptr, stride_h, stride_w, pad_h, pad_w, act, y, ws,
+                            kStaticWsBytes, stream);
+}
+
 extern "C" int ss_conv2d_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N, int32_t H, int32_t Wd,
                                  const void *packed, const float *bias, const void *residual, int32_t stride_h,
                                  int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act, void *y, void *workspace,
