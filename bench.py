@@ -5,7 +5,10 @@ A step is one launch of ss_conv2d_fwd (implicit unfold + sparse contraction + fu
 epilogue) on the ResNet-50-style 3x3 layer (N=32, 256->256, 14x14, fp16), with every operand
 already resident in device memory; the weight compressor is a one-off per weight update and is
 timed separately.  The dense twin is timed the same way for the speed-up ratio, and the CPU
-oracle is timed on the host cores as a reported baseline.  Prints ONE JSON line.
+oracle is timed on the host cores as a reported baseline.  Prints ONE JSON line; beside the
+headline it carries the rest of the protocol ("protocol": configs[0] latency, configs[2]
+bandwidth, cold-cache points, per-layer sums of configs[3] and configs[4]) and the rate against
+the issue peak measured in the same run.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail | --trunk | --fused | --q8]
         --table  per-layer report of configs 0-2, the ResNet-50 stack and ConvNeXt-T stage 1 (--cold, --only)
@@ -131,7 +134,7 @@ def q8_point(torch, ss, wl, L, steps, warmup, reps=3, dtype=None, korder=None):
     td = median_time(torch, run.densef, steps, warmup, reps=reps)
     tops = L.dense_equiv_flop / ts / 1e9
     return {"sparse_us": ts * 1e3, "dense_twin_us": td * 1e3, "speedup": td / ts, "tops": tops,
-            "frac_sparse_int8_peak": tops / SPARSE_INT8_PEAK_TOPS}
+            "frac_sparse_8bit_peak": tops / SPARSE_INT8_PEAK_TOPS}
 
 
 def print_q8_table(torch, ss, wl, steps, warmup):
@@ -390,6 +393,56 @@ def print_trunk(torch, ss, wl, batch=64, image=224):
         torch.cuda.empty_cache()
 
 
+def single_launch_us(torch, fn, reps=50):
+    """Latency of one isolated launch: device idle before, event pair around the launch, median over `reps`."""
+    ts = []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3)
+    return float(np.median(ts))
+
+
+def protocol_report(torch, ss, wl, steps, warmup):
+    """The rest of the measurement protocol beside the headline layer: configs[0] latency, configs[2] bandwidth, cold
+    points, and the per-layer sums of configs[3] (ResNet-50 convolutions, batch 64) and configs[4] (ConvNeXt-T stage
+    1, batch 128) against their roofline floors."""
+    out = {}
+    run0 = LayerRun(wl.CONFIG0, torch, ss, wl, values=False)
+    out["configs0"] = {"workload": wl.CONFIG0.name, "graph_us": median_time(torch, run0.sparse, steps, warmup, reps=3) * 1e3,
+                       "single_launch_us": single_launch_us(torch, run0.sparse),
+                       "dense_twin_graph_us": median_time(torch, run0.densef, steps, warmup, reps=3) * 1e3}
+    del run0
+    r2 = layer_report(torch, ss, wl, wl.CONFIG2, steps, warmup)
+    out["configs2"] = {"workload": wl.CONFIG2.name, "sparse_us": r2["sparse_us"], "dense_twin_us": r2["dense_us"],
+                       "speedup": r2["speedup"], "algorithmic_gbs": r2["gbs"], "frac_hbm_peak": r2["gbs"] / HBM_PEAK_GBS,
+                       "tflops": r2["tflops"], "floor_us": r2["t_floor_us"]}
+    cold = {}
+    for name, L in (("configs1", wl.CONFIG1), ("configs2", wl.CONFIG2)):
+        r = layer_report(torch, ss, wl, L, min(steps, 128), min(warmup, 20), cold=True)
+        cold[name] = {"sparse_us": r["sparse_us"], "dense_twin_us": r["dense_us"], "algorithmic_gbs": r["gbs"], "tflops": r["tflops"]}
+    out["cold"] = dict(cold, note="rotating through more than 512 MB of distinct activation / output buffers")
+    for key, title, layers in (("configs3", "ResNet-50 convolutions, batch 64, bf16, each layer on its own buffers", wl.resnet50_layers()),
+                               ("configs4", "ConvNeXt-T stage 1 masked layers, batch 128, bf16", wl.convnext_t_stage1_layers())):
+        tot_s = tot_d = tot_f = 0.0
+        per = []
+        for L in layers:
+            r = layer_report(torch, ss, wl, L, min(steps, 50), min(warmup, 10))
+            t_used = r.get("sparse_us", r["dense_us"])
+            tot_s += L.count * t_used
+            tot_d += L.count * r["dense_us"]
+            tot_f += L.count * r["t_floor_us"]
+            per.append({"layer": L.name, "count": L.count, "us": round(t_used, 2), "dense_twin_us": round(r["dense_us"], 2),
+                        "floor_us": round(r["t_floor_us"], 2), "gbs": round(r["gbs"]), "tflops": round(r["tflops"], 1)})
+        out[key] = {"workload": title, "sum_sparse_us": tot_s, "sum_dense_twin_us": tot_d, "sum_floor_us": tot_f,
+                    "speedup": tot_d / tot_s, "frac_of_floor": tot_f / tot_s, "layers": per}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -408,6 +461,7 @@ def main():
     ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n512", "cfg2"],
                     help="with --profile-run: which layer to launch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-protocol", action="store_true", help="skip the configs[0], [2], [3], [4] and cold-cache legs of the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the method has no multi-GPU path; batch sharding needs no "
@@ -463,7 +517,8 @@ def main():
     # graph (a launch lasts a few microseconds, less than the host needs to issue one), replayed
     # once between two events on the launch stream and bracketed by device synchronisation.
     kern_ms = time_graph(torch, run.sparse, args.steps, args.warmup)
-    ms = max(kern_ms, time_graph.last_wall_ms)
+    wall_ms = time_graph.last_wall_ms                  # host clock around the same replay (includes one synchronisation)
+    ms = kern_ms                                       # one clock for `value` and `roofline.achieved`: the event pair
     value = L.dense_equiv_flop / ms / 1e9              # dense-equivalent TFLOP/s
     eager_ms = time_launches(torch, run.sparse, args.steps, 2)   # host-issued launches, for reference
 
@@ -492,10 +547,13 @@ def main():
     tu = time_launches(torch, lambda: ss.ss_mask_update_compress(run.desc, Wu, Uz, run.M, packed=run.packed), 20, 3)
 
     achieved = L.dense_equiv_flop / kern_ms / 1e9
+    issue_peak = ss.ss_debug_issue_peak(ss.SS_F16, True)          # measured: register-only issue rate of the instruction
+    issue_peak_dense = ss.ss_debug_issue_peak(ss.SS_F16, False)
+    protocol = {} if args.no_protocol else protocol_report(torch, ss, wl, min(args.steps, 200), min(args.warmup, 50))
     out = {
         "metric": "dense-equiv TFLOP/s of 2:4 sparse conv2d; speedup vs same-design dense conv",
         "value": value, "unit": "TFLOP/s (dense-equivalent)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "ms_per_step": ms, "wall_ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "configs[1]: 3x3 conv 256->256, 14x14, N=32, stride 1, pad 1, fp16 NHWC, "
                                "argmax-of-logits 2:4 mask along Cin*kh*kw, fused bias+ReLU", "K": L.K, "P": L.P},
@@ -516,9 +574,16 @@ def main():
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": CFG1_TRAFFIC_BYTES,
                      "traffic_unit": "bytes per launch (algorithmic: %d)" % L.algorithmic_bytes(True),
+                     "traffic_source": "profiles/conv_kernel_cfg1_hbm_traffic.md (rocprofv3 FETCH_SIZE / WRITE_SIZE, L2 misses and "
+                                       "write-backs, not measured in this run)",
+                     "measured_issue_peak": issue_peak, "frac_vs_measured_issue_peak": achieved / issue_peak,
                      "kernel": "ss::conv_kernel (sparse, fp16)", "flop_per_launch": L.dense_equiv_flop,
                      "kernel_us": kern_ms * 1e3},
     }
+    out["measured_issue_peak"] = {"sparse_32x32x32_f16_tflops": issue_peak, "dense_32x32x16_f16_tflops": issue_peak_dense,
+                                  "note": "register-only probe, two waves per SIMD on every compute unit, dense-equivalent"}
+    out["scaled_batch_full_rounds"]["frac_vs_measured_issue_peak"] = Leven.dense_equiv_flop / te_s / 1e9 / issue_peak
+    out["protocol"] = protocol
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(L, wl)
     print(json.dumps(out), flush=True)

@@ -6,6 +6,7 @@
 #ifndef SS_DEBUG_H_
 #define SS_DEBUG_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -35,6 +36,15 @@ int ss_debug_force_split(int32_t n);
  * above.  Always returns SS_OK.  [host]
  */
 int ss_debug_limit_blocks(int32_t n);
+
+/*
+ * Calibration probe: measures the rate at which the chip issues the matrix instruction of the 16-bit kernels
+ * (sparse != 0: the 2:4-sparse 32x32x32 instruction, else the dense 32x32x16 one; dtype SS_F16 or SS_BF16) with
+ * operands and accumulators in registers only, two waves per SIMD on every compute unit, and writes it to *tflops
+ * [host] in dense-equivalent TFLOP/s.  `scratch` is device memory of at least 2048 bytes per compute unit (512 KiB
+ * on MI355X) that the probe may overwrite.  Waits for the stream.  SS_ERR_WORKSPACE when `scratch` is too small.
+ */
+int ss_debug_issue_peak(int32_t dtype, int32_t sparse, void *scratch, size_t scratch_bytes, float *tflops, void *stream);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,99 @@
+// Calibration probe: the rate at which a compute unit's SIMDs can issue the matrix instruction of the 16-bit kernels
+// when nothing has to be moved (operands and accumulators stay in registers).  The benchmark reports the convolution's
+// rate against this measured ceiling next to the published peak.
+#include "ss_internal.h"
+#include "../../include/ss_debug.h"
+#include <type_traits>
+
+namespace ss {
+
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 b16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b16x16 __attribute__((ext_vector_type(16)));
+typedef float acc16 __attribute__((ext_vector_type(16)));
+
+constexpr int kProbeAcc = 4;      // independent accumulators per wave: no instruction waits for the one before it
+
+template <int DT, bool SPARSE>
+__global__ __launch_bounds__(512) void issue_probe_kernel(float *sink, int iters)
+{
+    acc16 c[kProbeAcc];
+#pragma unroll
+    for (int i = 0; i < kProbeAcc; i++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) c[i][v] = 0.f;
+    // operands: built once, outside the timed loop
+    const float seed = (float)(threadIdx.x & 7) * 0.125f;
+    typename std::conditional<DT == SS_F16, h16x8, b16x8>::type a;
+    typename std::conditional<DT == SS_F16, h16x16, b16x16>::type b;
+    typedef typename std::conditional<DT == SS_F16, _Float16, __bf16>::type elem;
+#pragma unroll
+    for (int e = 0; e < 8; e++) a[e] = (elem)seed;
+#pragma unroll
+    for (int e = 0; e < 16; e++) b[e] = (elem)(seed + 1.f);
+    const auto blo = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4 * kProbeAcc; i4++) {
+            const int i = i4 % kProbeAcc;
+            if constexpr (DT == SS_F16) {
+                if constexpr (SPARSE) c[i] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(a, b, c[i], 0x4444, 0, 0);
+                else c[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, blo, c[i], 0, 0, 0);
+            } else {
+                if constexpr (SPARSE) c[i] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, c[i], 0x4444, 0, 0);
+                else c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, blo, c[i], 0, 0, 0);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kProbeAcc; i++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) s += c[i][v];
+    sink[blockIdx.x * 512 + threadIdx.x] = s;       // keeps the loop alive
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+extern "C" int ss_debug_issue_peak(int32_t dtype, int32_t sparse, void *scratch, size_t scratch_bytes, float *tflops, void *stream)
+{
+    if (!tflops || !scratch) return SS_ERR_INVALID_ARG;
+    if (dtype != SS_F16 && dtype != SS_BF16) return SS_ERR_UNSUPPORTED;
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0)
+        return SS_ERR_HIP;
+    const int blocks = ncu;                          // one workgroup of eight waves per compute unit: two waves per SIMD
+    if (scratch_bytes < (size_t)blocks * 512 * 4) return SS_ERR_WORKSPACE;
+    const int iters = 20000;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SS_ERR_HIP;
+    float *sink = static_cast<float *>(scratch);
+    auto launch = [&](int n) {
+        if (dtype == SS_F16) {
+            if (sparse) issue_probe_kernel<SS_F16, true><<<blocks, 512, 0, s>>>(sink, n);
+            else issue_probe_kernel<SS_F16, false><<<blocks, 512, 0, s>>>(sink, n);
+        } else {
+            if (sparse) issue_probe_kernel<SS_BF16, true><<<blocks, 512, 0, s>>>(sink, n);
+            else issue_probe_kernel<SS_BF16, false><<<blocks, 512, 0, s>>>(sink, n);
+        }
+    };
+    launch(100);                                     // warm-up
+    (void)hipEventRecord(e0, s);
+    launch(iters);
+    (void)hipEventRecord(e1, s);
+    int st = SS_OK;
+    float ms = 0.f;
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess || ms <= 0.f)
+        st = SS_ERR_HIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != SS_OK) return st;
+    // dense-equivalent operations: 2 * 32 * 32 * 32 per sparse instruction, 2 * 32 * 32 * 16 per dense one
+    const double flop = (double)blocks * 8 * iters * kProbeAcc * (sparse ? 65536.0 : 32768.0);
+    *tflops = (float)(flop / (ms * 1e-3) / 1e12);
+    return SS_OK;
+}
