@@ -267,7 +267,7 @@ int ss_conv2d_dense_res_fwd(const ss_weight_desc *desc, const void *x, int32_t N
  *   desc1   the first layer, 16-bit dtype.  Either k x k with k > 1: cout % 32 == 0, cout <= 256, and SS_K_CRS with a
  *           3x3 kernel and cin % 32 == 0, or SS_K_RSC with cin % 8 == 0.  Or 1x1 (the inverted bottleneck of a
  *           ConvNeXt block, narrow -> wide -> narrow: the wide intermediate is produced and consumed 128 channels
- *           at a time): stride 1, no padding, cin % 32 == 0, cin <= 128, cout % 128 == 0 (any width), bias1 16-byte
+ *           at a time): stride 1, no padding, cin % 32 == 0, cin <= 128, cout % 128 == 0 and cout <= 8192 (its bias sits in LDS), bias1 16-byte
  *           aligned, and desc2->cout <= 128.  Anything else: SS_ERR_UNSUPPORTED
  *   desc2   the 1x1 layer: same dtype, cin == desc1->cout, cout % 32 == 0
  *   packed1, packed2   written by ss_mask_compress for desc1 / desc2                         (read only)
@@ -281,6 +281,21 @@ int ss_conv2d_pw_fused_fwd(const ss_weight_desc *desc1, const void *x, int32_t N
                            int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t act1,
                            const ss_weight_desc *desc2, const void *packed2, const float *bias2,
                            const void *residual, int32_t act2, void *y, void *stream);
+
+/*
+ * Would ss_conv2d_pw_fused_fwd (sparse != 0) or ss_conv2d_pw_fused_dense_fwd (sparse == 0) take this pair of layers,
+ * and does the library expect the fused kernel to be faster than the two separate calls?  Answers from the
+ * descriptors and the first layer's stride and padding alone; [host], touches no device.
+ *   *supported  1 when the fused entry point accepts the pair (same conditions as listed there), else 0
+ *   *pays       1 when, on the library's own measurements, the fused kernel beats the two calls: always for the
+ *               1x1 -> 1x1 pair; for a k x k -> 1x1 pair while the first layer is at most 128 channels wide on the
+ *               sparse path (64 on the dense twin).  A caller that chains layers fuses where pays is 1.
+ * Returns SS_ERR_INVALID_ARG for null pointers, malformed descriptors, or a second layer that is not a 1x1
+ * convolution on the first one's output channels.
+ */
+int ss_conv2d_pw_fused_query(const ss_weight_desc *desc1, int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                             const ss_weight_desc *desc2, int32_t sparse, int32_t *supported /*[host] out*/,
+                             int32_t *pays /*[host] out*/);
 
 /* The dense twin of ss_conv2d_pw_fused_fwd (operands built by ss_dense_pack). */
 int ss_conv2d_pw_fused_dense_fwd(const ss_weight_desc *desc1, const void *x, int32_t N, int32_t H, int32_t Wd,

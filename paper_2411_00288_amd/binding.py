@@ -24,7 +24,7 @@ EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_com
            "ss_dense_pack", "ss_conv2d_workspace_bytes", "ss_conv2d_fwd", "ss_conv2d_dense_fwd",
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
            "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd",
-           "ss_weights_check", "ss_conv2d_fwd_static_ws"]
+           "ss_weights_check", "ss_conv2d_fwd_static_ws", "ss_conv2d_pw_fused_query"]
 DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks", "ss_debug_force_split", "ss_debug_issue_peak"]          # include/ss_debug.h: test hooks
 
 
@@ -72,6 +72,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_conv2d_pw_fused_fwd.argtypes = fused_args
     lib.ss_conv2d_pw_fused_dense_fwd.argtypes = fused_args
     lib.ss_weights_check.argtypes = [dp, vp, i32, vp]
+    lib.ss_conv2d_pw_fused_query.argtypes = [dp, i32, i32, i32, i32, dp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.ss_conv2d_fwd_static_ws.argtypes = conv_args[:13] + [vp]            # no workspace pair
     lib.ss_debug_force_tile.argtypes = [i32]
     lib.ss_debug_limit_blocks.argtypes = [i32]
@@ -477,6 +478,16 @@ def prepare_conv2d_pw_fused(desc1, x, w1, bias1, stride, pad, act1, desc2, w2, b
         if st != SS_OK:
             raise SSError(st, what)
     return launch, y
+
+
+def ss_conv2d_pw_fused_query(desc1, stride, pad, desc2, sparse=True):
+    """(supported, pays): would the fused entry point take this pair, and does the library expect it to beat two calls?"""
+    sup, pays = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = _lib.ss_conv2d_pw_fused_query(ctypes.byref(desc1), stride[0], stride[1], pad[0], pad[1], ctypes.byref(desc2),
+                                       1 if sparse else 0, ctypes.byref(sup), ctypes.byref(pays))
+    if st != SS_OK:
+        raise SSError(st, "ss_conv2d_pw_fused_query")
+    return bool(sup.value), bool(pays.value)
 
 
 def ss_conv2d_pw_fused_fwd(desc1, x, packed1, bias1, stride, pad, act1, desc2, packed2, bias2=None, residual=None,

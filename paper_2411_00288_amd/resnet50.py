@@ -99,7 +99,6 @@ class Trunk:
             wbuf = ss.ss_mask_compress(desc, W, M) if use_sparse else ss.ss_dense_pack(desc, W, M)
             prepared[op.name] = (desc, wbuf, bias, use_sparse)
         by_dst = {op.dst: op for op in self.ops}
-        max_width = 128 if sparse else 64
         pos = {}                                            # op name -> index of its launch
         for op in self.ops:
             if op.kind == "pool":
@@ -111,7 +110,9 @@ class Trunk:
             prev = by_dst.get(op.src)
             res = None if op.residual is None else self.bufs[op.residual]
             if (fuse_pairs and op.name.endswith("_c3") and prev is not None and prev.name.endswith("_c2") and
-                    prev.layer.cout <= max_width and prepared[prev.name][3] == use_sparse):
+                    prepared[prev.name][3] == use_sparse and
+                    all(ss.ss_conv2d_pw_fused_query(prepared[prev.name][0], (prev.layer.stride,) * 2, (prev.layer.pad,) * 2,
+                                                    desc, use_sparse))):      # the library says: supported, and expected to pay
                 # (decided here, at the 1x1's position in the order: its residual is ready by now)
                 d1, w1, b1, _ = prepared[prev.name]
                 P = prev.layer
