@@ -10,12 +10,13 @@ headline it carries the rest of the protocol ("protocol": configs[0] latency, co
 bandwidth, cold-cache points, per-layer sums of configs[3] and configs[4]) and the rate against
 the issue peak measured in the same run.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail | --trunk | --fused | --q8]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--table | --tail | --trunk | --fused | --q8 | --probes]
         --table  per-layer report of configs 0-2, the ResNet-50 stack and ConvNeXt-T stage 1 (--cold, --only)
         --tail   the fused residual / activation tail against a separate pass
         --trunk  the ResNet-50 convolution trunk chained in one HIP graph, images/s
         --fused  a k x k convolution and the 1x1 after it (or the two 1x1 of a ConvNeXt block) in one kernel
         --q8     the int8 / FP8 precision points
+        --probes calibration: register-only issue rate of the matrix instructions, LDS bandwidth of a compute unit
 """
 from __future__ import annotations
 
@@ -35,9 +36,9 @@ SPARSE_PEAK_TFLOPS = 5000.0   # 2:4-sparse fp16/bf16 MFMA, dense-equivalent = 2 
 DENSE_PEAK_TFLOPS = 2500.0
 SPARSE_INT8_PEAK_TOPS = 10000.0     # 2 x the published dense int8 peak (5.0 POP/s), dense-equivalent
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the sparse kernel on configs[1], from the rocprofv3 counter runs summarised in
-# profiles/conv_kernel_cfg1_hbm_traffic.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (factors from a streaming copy).
-CFG1_TRAFFIC_BYTES = int((2.0 * 4328.0 + 1.0 * 3136.0) * 1024)
+# Memory-side bytes per launch of the sparse kernel on configs[1], from the rocprofv3 counter runs summarised in
+# profiles/conv_kernel_hbm_traffic.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (factors from a streaming copy).
+CFG1_TRAFFIC_BYTES = int((2.0 * 4325.1 + 1.0 * 3136.0) * 1024)
 
 
 def _to_dev(bits, dtype, torch, ss):
@@ -443,6 +444,20 @@ def protocol_report(torch, ss, wl, steps, warmup):
     return out
 
 
+def print_probes(torch, ss):
+    """Calibration probes of the library (include/ss_debug.h): what the chip delivers when nothing else is in the way."""
+    print("## register-only issue rate of the matrix instruction (two waves per SIMD on every compute unit), dense-equivalent TFLOP/s")
+    for name, dt in (("fp16", ss.SS_F16), ("bf16", ss.SS_BF16)):
+        print(f"{name}: 2:4-sparse 32x32x32 {ss.ss_debug_issue_peak(dt, True):8.1f}   dense 32x32x16 {ss.ss_debug_issue_peak(dt, False):8.1f}", flush=True)
+    print("## LDS bandwidth of one compute unit, 16 bytes per lane and instruction, eight instructions in flight per wave; "
+          "B/clk at the nominal 2.4 GHz")
+    for write, what, rows in ((False, "fragment reads", (592, 576, 272, 144)), (True, "lane-linear writes", (16,))):
+        for rb in rows:
+            vals = [ss.ss_debug_lds_bandwidth(write, w, rb) for w in (1, 2, 4)]
+            row = f"{what:20s}" + (f" rows of {rb:3d} B" if not write else "              ")
+            print(row + "  " + "  ".join(f"{w} wave(s)/SIMD: {v:6.1f} GB/s = {v / 2.4:5.1f} B/clk" for w, v in zip((1, 2, 4), vals)), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -458,8 +473,9 @@ def main():
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
                          "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n512", "cfg2"],
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n500", "cfg1_n512", "cfg2", "s1_c3"],
                     help="with --profile-run: which layer to launch")
+    ap.add_argument("--probes", action="store_true", help="calibration probes (matrix-instruction issue rate, LDS bandwidth) instead of the JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-protocol", action="store_true", help="skip the configs[0], [2], [3], [4] and cold-cache legs of the JSON line")
     args = ap.parse_args()
@@ -476,6 +492,9 @@ def main():
     from paper_2411_00288_amd import workloads as wl
     torch.cuda.set_device(0)
 
+    if args.probes:
+        print_probes(torch, ss)
+        return
     if args.trunk:
         print_trunk(torch, ss, wl)
         return
@@ -494,7 +513,9 @@ def main():
 
     L = wl.CONFIG1
     if args.profile_run:
-        L = {"cfg1": wl.CONFIG1, "cfg1_n512": wl.with_batch(wl.CONFIG1, 512), "cfg2": wl.CONFIG2}[args.workload]
+        L = {"cfg1": wl.CONFIG1, "cfg1_n500": wl.with_batch(wl.CONFIG1, 500), "cfg1_n512": wl.with_batch(wl.CONFIG1, 512),
+             "cfg2": wl.CONFIG2,
+             "s1_c3": [l for l in wl.resnet50_layers() if l.name == "s1_c3_1x1_64_256"][0]}[args.workload]
     run = LayerRun(L, torch, ss, wl, values=not args.profile_run)
 
     if args.profile_run:
@@ -574,7 +595,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / SPARSE_PEAK_TFLOPS, "traffic": CFG1_TRAFFIC_BYTES,
                      "traffic_unit": "bytes per launch (algorithmic: %d)" % L.algorithmic_bytes(True),
-                     "traffic_source": "profiles/conv_kernel_cfg1_hbm_traffic.md (rocprofv3 FETCH_SIZE / WRITE_SIZE, L2 misses and "
+                     "traffic_source": "profiles/conv_kernel_hbm_traffic.md (rocprofv3 FETCH_SIZE / WRITE_SIZE, L2 misses and "
                                        "write-backs, not measured in this run)",
                      "measured_issue_peak": issue_peak, "frac_vs_measured_issue_peak": achieved / issue_peak,
                      "kernel": "ss::conv_kernel (sparse, fp16)", "flop_per_launch": L.dense_equiv_flop,

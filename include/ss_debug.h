@@ -46,6 +46,16 @@ int ss_debug_limit_blocks(int32_t n);
  */
 int ss_debug_issue_peak(int32_t dtype, int32_t sparse, void *scratch, size_t scratch_bytes, float *tflops, void *stream);
 
+/*
+ * Calibration probe: LDS bandwidth of one compute unit in GB/s (divide by the clock in GHz for bytes per clock),
+ * with one workgroup per compute unit and `waves_per_simd` (1, 2 or 4) waves per SIMD, each issuing eight independent
+ * 16-byte-per-lane instructions between waits.  write == 0: reads in the convolution kernels' fragment pattern over
+ * pixel rows of `row_bytes` (a multiple of 16, at most 592); write != 0: lane-linear writes.  `scratch` as for
+ * ss_debug_issue_peak, 4096 bytes per compute unit.  Waits for the stream.
+ */
+int ss_debug_lds_bandwidth(int32_t write, int32_t waves_per_simd, int32_t row_bytes, void *scratch, size_t scratch_bytes,
+                           float *gb_per_s_per_cu, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = ["ss_status_string", "ss_packed_bytes", "ss_dense_bytes", "ss_mask_com
            "ss_conv2d_res_fwd", "ss_conv2d_dense_res_fwd", "ss_mask_update_compress", "ss_maxpool2d", "ss_dwconv2d_fwd",
            "ss_conv2d_q8_fwd", "ss_conv2d_q8_dense_fwd", "ss_conv2d_pw_fused_fwd", "ss_conv2d_pw_fused_dense_fwd",
            "ss_weights_check", "ss_conv2d_fwd_static_ws", "ss_conv2d_pw_fused_query"]
-DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks", "ss_debug_force_split", "ss_debug_issue_peak"]          # include/ss_debug.h: test hooks
+DEBUG_EXPORTS = ["ss_debug_force_tile", "ss_debug_limit_blocks", "ss_debug_force_split", "ss_debug_issue_peak", "ss_debug_lds_bandwidth"]          # include/ss_debug.h: test hooks
 
 
 class ss_weight_desc(ctypes.Structure):
@@ -78,6 +78,7 @@ def _load() -> ctypes.CDLL:
     lib.ss_debug_limit_blocks.argtypes = [i32]
     lib.ss_debug_force_split.argtypes = [i32]
     lib.ss_debug_issue_peak.argtypes = [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
+    lib.ss_debug_lds_bandwidth.argtypes = [i32, i32, i32, vp, sz, ctypes.POINTER(ctypes.c_float), vp]
     for name in EXPORTS[1:] + DEBUG_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -244,6 +245,17 @@ def ss_debug_issue_peak(dtype: int = SS_F16, sparse: bool = True, stream=None) -
                                   ctypes.byref(out), _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_debug_issue_peak")
+    return float(out.value)
+
+
+def ss_debug_lds_bandwidth(write: bool, waves_per_simd: int, row_bytes: int = 592, stream=None) -> float:
+    """Calibration probe (include/ss_debug.h): LDS bandwidth of one compute unit, GB/s."""
+    scratch = torch.empty(2 << 20, dtype=torch.uint8, device="cuda")
+    out = ctypes.c_float(0.0)
+    st = _lib.ss_debug_lds_bandwidth(1 if write else 0, int(waves_per_simd), int(row_bytes), _dev_ptr(scratch, "scratch"),
+                                     scratch.numel(), ctypes.byref(out), _stream_ptr(stream))
+    if st != SS_OK:
+        raise SSError(st, "ss_debug_lds_bandwidth")
     return float(out.value)
 
 

@@ -54,6 +54,41 @@ __global__ __launch_bounds__(512) void issue_probe_kernel(float *sink, int iters
     sink[blockIdx.x * 512 + threadIdx.x] = s;       // keeps the loop alive
 }
 
+// LDS bandwidth of a compute unit: every wave issues eight independent 16-byte-per-lane LDS instructions, waits for
+// them, and repeats.  MODE 0: reads in the convolution kernels' fragment pattern (lane % 32 = pixel row of `row_bytes`,
+// lane / 32 = second half of the step); MODE 1: lane-linear writes (a wave's 1 KiB contiguous).
+typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
+template <int MODE>
+__global__ __launch_bounds__(1024) void lds_probe_kernel(uint32_t *sink, int iters, int row_bytes)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    for (int i = t; i < 65536 / 4; i += blockDim.x) reinterpret_cast<uint32_t *>(lds)[i] = (uint32_t)i;
+    __syncthreads();
+    // byte offsets stay below 64 KiB: rows 0..63 of at most 592 bytes plus 8 x 64 bytes; 16 KiB + 3 x 16 KiB for the writes
+    // (the LDS instructions are written out: the probe must issue exactly these, eight in flight, then one wait)
+    const uint32_t base = (uint32_t)(uintptr_t)lds;
+    const uint32_t rd = base + (lane & 31) * row_bytes + (lane >> 5) * 32 + (w & 1) * 32 * row_bytes;
+    const uint32_t wr = base + lane * 16 + (w & 15) * 1024;
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; it++) {
+        if constexpr (MODE == 0) {
+            pu32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v[j]) : "v"(rd), "n"(j * 64));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc ^= v[j][0];
+        } else {
+            const pu32x4 d = {acc, (uint32_t)it, 1u, 2u};
+#pragma unroll
+            for (int j = 0; j < 8; j++) asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(wr), "v"(d), "n"((j % 3) * 16384) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    }
+    sink[blockIdx.x * 1024 + t] = acc;
+}
+
 }  // namespace ss
 
 using namespace ss;
@@ -95,5 +130,38 @@ extern "C" int ss_debug_issue_peak(int32_t dtype, int32_t sparse, void *scratch,
     // dense-equivalent operations: 2 * 32 * 32 * 32 per sparse instruction, 2 * 32 * 32 * 16 per dense one
     const double flop = (double)blocks * 8 * iters * kProbeAcc * (sparse ? 65536.0 : 32768.0);
     *tflops = (float)(flop / (ms * 1e-3) / 1e12);
+    return SS_OK;
+}
+
+extern "C" int ss_debug_lds_bandwidth(int32_t write, int32_t waves_per_simd, int32_t row_bytes, void *scratch, size_t scratch_bytes,
+                                      float *gb_per_s_per_cu, void *stream)
+{
+    if (!gb_per_s_per_cu || !scratch) return SS_ERR_INVALID_ARG;
+    if (waves_per_simd != 1 && waves_per_simd != 2 && waves_per_simd != 4) return SS_ERR_INVALID_ARG;
+    if (row_bytes < 16 || row_bytes > 592 || row_bytes % 16 != 0) return SS_ERR_INVALID_ARG;
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0)
+        return SS_ERR_HIP;
+    if (scratch_bytes < (size_t)ncu * 1024 * 4) return SS_ERR_WORKSPACE;
+    const int threads = 256 * waves_per_simd, iters = 2000;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto kern = write ? lds_probe_kernel<1> : lds_probe_kernel<0>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 65536) != hipSuccess) return SS_ERR_HIP;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SS_ERR_HIP;
+    uint32_t *sink = static_cast<uint32_t *>(scratch);
+    kern<<<ncu, threads, 65536, s>>>(sink, 10, row_bytes);
+    (void)hipEventRecord(e0, s);
+    kern<<<ncu, threads, 65536, s>>>(sink, iters, row_bytes);
+    (void)hipEventRecord(e1, s);
+    int st = SS_OK;
+    float ms = 0.f;
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess || ms <= 0.f)
+        st = SS_ERR_HIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != SS_OK) return st;
+    const double bytes_per_cu = (double)iters * 8 * 64 * 16 * (threads / 64);     // per workgroup = per compute unit
+    *gb_per_s_per_cu = (float)(bytes_per_cu / (ms * 1e-3) / 1e9);
     return SS_OK;
 }
