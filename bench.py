@@ -473,7 +473,7 @@ def main():
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
                          "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n500", "cfg1_n512", "cfg2", "s1_c3"],
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n500", "cfg1_n512", "cfg2", "s1_c3", "stem"],
                     help="with --profile-run: which layer to launch")
     ap.add_argument("--probes", action="store_true", help="calibration probes (matrix-instruction issue rate, LDS bandwidth) instead of the JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -515,7 +515,8 @@ def main():
     if args.profile_run:
         L = {"cfg1": wl.CONFIG1, "cfg1_n500": wl.with_batch(wl.CONFIG1, 500), "cfg1_n512": wl.with_batch(wl.CONFIG1, 512),
              "cfg2": wl.CONFIG2,
-             "s1_c3": [l for l in wl.resnet50_layers() if l.name == "s1_c3_1x1_64_256"][0]}[args.workload]
+             "s1_c3": [l for l in wl.resnet50_layers() if l.name == "s1_c3_1x1_64_256"][0],
+             "stem": wl.resnet50_layers()[0]}[args.workload]
     run = LayerRun(L, torch, ss, wl, values=not args.profile_run)
 
     if args.profile_run:
@@ -525,9 +526,10 @@ def main():
         torch.mul(src, 1.0, out=dst)                                       # a plain streaming copy kernel
         torch.cuda.synchronize()
         del src, dst
-        for _ in range(20):
-            run.sparse()
-        torch.cuda.synchronize()
+        if L.mask != "none":
+            for _ in range(20):
+                run.sparse()
+            torch.cuda.synchronize()
         for _ in range(20):
             run.densef()
         torch.cuda.synchronize()

@@ -2,6 +2,7 @@
 // including file through SS_INST_NAME / SS_INST_DT / SS_INST_SPARSE / SS_INST_FUSED.
 #include "ss_conv_kernel.h"
 #include "ss_conv_stream.h"
+#include "ss_conv_image.h"
 
 #define SS_CAT2(a, b) a##b
 #define SS_CAT(a, b) SS_CAT2(a, b)
@@ -24,6 +25,16 @@ int SS_CAT(conv_dispatch_, SS_INST_NAME)(const ss_weight_desc *desc, const ConvP
             if (forced == 10 || (forced < 0 && pays && tiles >= 2ll * ncu))
                 return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 4>(p, ncu, s);
             if (forced == 11) return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 2>(p, ncu, s);
+        }
+    }
+    if constexpr (!is_byte_type(SS_INST_DT) && !SS_INST_SPARSE) {
+        // the dense first layer of an image network (tile id 12 when forced)
+        const int forced = forced_tile();
+        if ((forced < 0 || forced == 12) && image_eligible(desc, p)) {
+            int ncu = compute_units();
+            if (ncu <= 0) return SS_ERR_HIP;
+            if (block_limit() > 0 && block_limit() < ncu) ncu = block_limit();
+            return launch_image<SS_INST_DT>(desc, p, ncu, s);
         }
     }
     return pick_mode<SS_INST_DT, SS_INST_SPARSE>(desc, p, s);

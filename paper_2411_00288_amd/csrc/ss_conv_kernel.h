@@ -116,16 +116,26 @@ __device__ __forceinline__ Acc<DT> mma_dense(u32x4 a, u32x4 b, Acc<DT> c)
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// Two fp32 values to one dword of 16-bit floats, round to nearest even, in one instruction (V_CVT_PK_F16_F32 /
+// V_CVT_PK_BF16_F32).
 template <int DT>
 __device__ __forceinline__ uint32_t cvt_pack2(float a, float b)
 {
-    if constexpr (DT == SS_F16) {
-        _Float16 ha = (_Float16)a, hb = (_Float16)b;   // round-to-nearest-even
-        return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
-    } else {
-        __bf16 ha = (__bf16)a, hb = (__bf16)b;         // round-to-nearest-even
-        return (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
-    }
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {a, b};
+    if constexpr (DT == SS_F16)
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    else
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// max(v, floor) that hands a NaN through (the IEEE 754-2019 maximum, one V_MAXIMUM3_F32): ReLU with floor = 0, the
+// identity with floor = -inf.  (A sum of exactly -0 comes out as +0.)
+__device__ __forceinline__ float floor_at(float v, float floor)
+{
+    return __builtin_elementwise_maximum(v, floor);
 }
 
 // Exact value of a 16-bit pattern as fp32.
@@ -746,7 +756,7 @@ void conv_kernel(ConvParams p)
     const float relu_floor = p.act == SS_ACT_RELU ? 0.f : -__builtin_inff();
     // ReLU when relu_floor = 0, identity when -inf (a NaN passes through); GELU = z * Phi(z) with the exact normal
     // CDF, written with erfc so that the lower tail keeps its relative accuracy
-    auto relu_or_id = [&](float v) { return v < relu_floor ? 0.f : v; };
+    auto relu_or_id = [&](float v) { return floor_at(v, relu_floor); };
     auto gelu = [](float v) { return gelu_erfc(v); };
     if constexpr (CAN_SPLIT) {
         if (nsplit > 1) {

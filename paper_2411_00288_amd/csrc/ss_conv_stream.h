@@ -341,7 +341,7 @@ void conv3x3_stream_kernel(ConvParams p, int tiles_n, int slots_n)
         }
         const int n0 = (nslot + it * slots_n) * BN;
         if (p.act == SS_ACT_GELU) write_tile(n0, [](float v) { return gelu_erfc(v); });
-        else write_tile(n0, [&](float v) { return v < relu_floor ? 0.f : v; });     // ReLU, or the identity with a floor of -inf (a NaN passes)
+        else write_tile(n0, [&](float v) { return floor_at(v, relu_floor); });     // ReLU, or the identity with a floor of -inf (a NaN passes)
         init_acc();
     }
 }
