@@ -206,7 +206,10 @@ struct ChunkShape {
     // is left unpadded (36 vectors) and the index of a 16-byte vector inside its row is XOR-ed with bits 2..3 of the
     // pixel row (SWZ): the vector stays inside its aligned group of four, and both the transposed writes (4 pixel
     // rows x 4 units per 16 lanes) and the fragment reads (16 consecutive pixel rows) cover all 64 banks exactly once.
-    static constexpr bool SWZ = MODE == MODE_TAPS && TAPS == 9;
+    // Only in the deep variants: the swizzled addresses cost the shallow 128 x 64 kernel eight registers, which is the
+    // step from four to three waves per SIMD (its fused form ran 35 -> 49 us with it); the deep variants run at one to
+    // three waves per SIMD anyway.
+    static constexpr bool SWZ = MODE == MODE_TAPS && TAPS == 9 && DEEP;
     static constexpr int ROW = SWZ ? BK : BK + 8;
     // LDS copies of the chunk: double-buffered, so that the next chunk is written while this one is
     // multiplied -- except for the large unfolded 3x3 chunk in the shallow variant, which is kept once
