@@ -3,6 +3,7 @@
 #include "ss_conv_kernel.h"
 #include "ss_conv_stream.h"
 #include "ss_conv_image.h"
+#include "ss_conv_rows.h"
 
 #define SS_CAT2(a, b) a##b
 #define SS_CAT(a, b) SS_CAT2(a, b)
@@ -25,6 +26,22 @@ int SS_CAT(conv_dispatch_, SS_INST_NAME)(const ss_weight_desc *desc, const ConvP
             if (forced == 10 || (forced < 0 && pays && tiles >= 2ll * ncu))
                 return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 4>(p, ncu, s);
             if (forced == 11) return launch_stream<SS_INST_DT, SS_INST_SPARSE, 2, 2>(p, ncu, s);
+        }
+    }
+    if constexpr (!is_byte_type(SS_INST_DT)) {
+        // 1x1 layers with short reductions and many output channels: activations stationary (tile id 13 when forced)
+        const int forced = forced_tile();
+        // Measured on the ResNet-50 / ConvNeXt-T layers: it pays for the channel-expanding layers (64 -> 256 ... 512 -> 2048
+        // and the 512 -> 1024 projection: 5-13 % faster; 96 -> 384 with GELU: 117 -> 84 us) and loses on the reducing
+        // ones, whose few output channels leave nothing to walk over.
+        // With a residual tail the gain is smaller (the residual runs are fetched by the same waves that multiply), and
+        // at 512 channels, where LDS leaves room for one workgroup per compute unit, it turns into a loss.
+        const bool pays = p.Cout >= 2 * desc->cin && p.Cout >= 256 && !(desc->cin >= 512 && p.residual != nullptr);
+        if ((forced == 13 || (forced < 0 && pays)) && rows_eligible(desc, p)) {
+            int ncu = compute_units();
+            if (ncu <= 0) return SS_ERR_HIP;
+            if (block_limit() > 0 && block_limit() < ncu) ncu = block_limit();
+            return launch_rows<SS_INST_DT, SS_INST_SPARSE>(desc, p, ncu, s);
         }
     }
     if constexpr (!is_byte_type(SS_INST_DT) && !SS_INST_SPARSE) {

@@ -100,6 +100,7 @@ inline SplitPlan plan_split(const ss_weight_desc *d, long long P, int Ks, int nc
     SplitPlan pl{};
     pl.nsplit = 1;
     if (is_byte_type(d->dtype)) return pl;
+    if (forced_tile >= 10) return pl;              // the resident-grid, image and activation-stationary kernels do not split
     const bool pw = d->kh * d->kw == 1 && d->cin % 8 == 0 && Ks > 2;
     const bool taps = d->korder == SS_K_CRS && d->kh == 3 && d->kw == 3 && d->cin % 32 == 0;
     if (!pw && !taps) return pl;

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from paper_2411_00288_amd import workloads as wl
-from helpers import check_close, dev_bits, host_bits
+from helpers import ELT_TOL, REL_L2_TOL, check_close, dev_bits, host_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -97,13 +97,15 @@ def test_fused_pair_matches_oracle_chain(ss, force_tile, pair, with_res):
             assert rel <= 4e-3, f"{what}: rel-L2 {rel:.3e}"
             assert (np.abs(got - ref) <= 2e-2 * (np.abs(ref) + 1)).all(), what
             # The second layer alone, at the single-layer bound: the oracle's 1x1 layer fed the intermediate the GPU
-            # itself produced (the separate first call's output, which the fused kernel keeps on chip bit for bit).
+            # itself produced (the separate first call's output; the fused kernel's on-chip intermediate is the same
+            # sum, possibly added up in another order by another kernel, i.e. equal up to a rounding of the intermediate).
             ref2 = oracle.conv2d(host_bits(t_gpu), d2["W"], d2["M"], cin=L2.cin, kh=1, kw=1, korder=L2.korder,
                                  dtype=L2.dtype, bias=d2["bias"], act=L2.act, residual=res_bits)
             check_close(y, ref2, what + " (second layer on the GPU's intermediate)")
-            # against the library's own two separate calls the difference is one rounding of the output at most
+            # against the library's own two separate calls: roundings of the intermediate and of the output apart
             sep = y_sep.float().cpu().numpy().astype(np.float64)
-            assert (np.abs(got - sep) <= 2.0 ** -7 * (np.abs(sep) + 1e-3)).all(), what
+            assert (np.abs(got - sep) <= ELT_TOL * (np.abs(sep) + 1)).all(), what
+            assert np.linalg.norm(got - sep) <= REL_L2_TOL * np.linalg.norm(sep), what
 
 
 @pytest.mark.parametrize("cmid", [64, 128, 256])
