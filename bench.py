@@ -451,7 +451,8 @@ def print_probes(torch, ss):
         print(f"{name}: 2:4-sparse 32x32x32 {ss.ss_debug_issue_peak(dt, True):8.1f}   dense 32x32x16 {ss.ss_debug_issue_peak(dt, False):8.1f}", flush=True)
     print("## LDS bandwidth of one compute unit, 16 bytes per lane and instruction, eight instructions in flight per wave; "
           "B/clk at the nominal 2.4 GHz")
-    for write, what, rows in ((False, "fragment reads", (592, 576, 272, 144)), (True, "lane-linear writes", (16,))):
+    for write, what, rows in ((0, "fragment reads", (592, 576, 272, 144)), (1, "lane-linear writes", (16,)),
+                              (2, "... as 8-byte writes", (16,)), (3, "... as 4-byte writes", (16,))):
         for rb in rows:
             vals = [ss.ss_debug_lds_bandwidth(write, w, rb) for w in (1, 2, 4)]
             row = f"{what:20s}" + (f" rows of {rb:3d} B" if not write else "              ")

@@ -248,11 +248,11 @@ def ss_debug_issue_peak(dtype: int = SS_F16, sparse: bool = True, stream=None) -
     return float(out.value)
 
 
-def ss_debug_lds_bandwidth(write: bool, waves_per_simd: int, row_bytes: int = 592, stream=None) -> float:
+def ss_debug_lds_bandwidth(write: int, waves_per_simd: int, row_bytes: int = 592, stream=None) -> float:
     """Calibration probe (include/ss_debug.h): LDS bandwidth of one compute unit, GB/s."""
     scratch = torch.empty(2 << 20, dtype=torch.uint8, device="cuda")
     out = ctypes.c_float(0.0)
-    st = _lib.ss_debug_lds_bandwidth(1 if write else 0, int(waves_per_simd), int(row_bytes), _dev_ptr(scratch, "scratch"),
+    st = _lib.ss_debug_lds_bandwidth(int(write), int(waves_per_simd), int(row_bytes), _dev_ptr(scratch, "scratch"),
                                      scratch.numel(), ctypes.byref(out), _stream_ptr(stream))
     if st != SS_OK:
         raise SSError(st, "ss_debug_lds_bandwidth")

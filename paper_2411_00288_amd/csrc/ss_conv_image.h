@@ -242,9 +242,10 @@ void conv_image_kernel(ConvParams p, int tiles_h, int tiles_w, int ntiles)
         }
 
         // ---- epilogue: activation, one rounding, slab, 16-byte stores
+        // (A wave's LDS operations execute in order: a piece's reads see its writes, and the next piece may be written
+        // as soon as this one's reads are issued -- its conversion and writes then cover the slab's read latency.)
         auto write_out = [&](auto actf) {
-#pragma unroll
-            for (int c = 0; c < 2; c++) {
+            auto put = [&](int c) {
 #pragma unroll
                 for (int tm = 0; tm < 2; tm++)
 #pragma unroll
@@ -255,15 +256,24 @@ void conv_image_kernel(ConvParams p, int tiles_h, int tiles_w, int ntiles)
                         *reinterpret_cast<uint2 *>(slab + n32 * SH::SLAB_ROW + 32 * tm + 8 * j + 4 * g) =
                             make_uint2(cvt_pack2<DT>(rr[0], rr[1]), cvt_pack2<DT>(rr[2], rr[3]));
                     }
-                // (a wave's LDS operations execute in order: the reads below see the writes above)
+            };
+            put(0);
+#pragma unroll
+            for (int c = 0; c < 2; c++) {
+                u32x4 w[4];
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
                     const int q = lane + 64 * i, px = q >> 3, run = q & 7;
-                    const u32x4 w = *reinterpret_cast<const u32x4 *>(slab + px * SH::SLAB_ROW + run * 8);
+                    w[i] = *reinterpret_cast<const u32x4 *>(slab + px * SH::SLAB_ROW + run * 8);
+                }
+                if (c == 0) put(1);
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int q = lane + 64 * i, px = q >> 3, run = q & 7;
                     const int ho = ho0 + 2 * c + (px >> 4), wo = wo0 + (px & 15), o = m0 + run * 8;
                     const bool ok = ho < p.Ho && wo < p.Wo && o < p.Cout;
                     const unsigned off = ((unsigned)((n * p.Ho + ho) * p.Wo + wo) * (unsigned)p.Cout + (unsigned)o) * 2u;
-                    __builtin_amdgcn_raw_buffer_store_b128(w, ry, (int)(ok ? off : kOutOfRange), 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(w[i], ry, (int)(ok ? off : kOutOfRange), 0, 0);
                 }
             }
         };

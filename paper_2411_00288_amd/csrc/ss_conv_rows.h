@@ -197,23 +197,32 @@ void conv_pw_rows_kernel(ConvParams p, int mg, int pairs_per_group)
         // ---- epilogue: 2 x 2 tiles of 32 channels x 32 pixels through the slab, fp32; residual, activation, rounding
         // (the residual runs of tile t + 1 are fetched while tile t is written; those of tile 0 were fetched before the
         // reduction, see above)
+        // (A wave's LDS operations execute in order: a piece's reads see its writes, and the next piece may be written
+        // as soon as this one's reads are issued -- its writes then cover part of the slab's read latency.)
         auto write_out = [&](auto actf) {
-#pragma unroll
-            for (int t = 0; t < 4; t++) {
+            auto put = [&](int t) {
                 const int tm = t >> 1, tn = t & 1;
-                if (has_res && t + 1 < 4) load_res(res[(t + 1) & 1], rp, t + 1);
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     *reinterpret_cast<f32x4 *>(slab + c2 * SH::SLAB_ROW + 8 * q + 4 * g2) =
                         f32x4{acc[tm][tn][4 * q + 0], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2], acc[tm][tn][4 * q + 3]};
-                // (a wave's LDS operations execute in order: the reads below see the writes above)
+            };
+            put(0);
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                if (has_res && t + 1 < 4) load_res(res[(t + 1) & 1], rp, t + 1);
+                f32x4 lo[2], hi[2];
 #pragma unroll
                 for (int j = 0; j < 2; j++) {
                     const int it = lane + 64 * j;
                     const int px = it >> 2, run = it & 3;
-                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(slab + px * SH::SLAB_ROW + run * 8);
-                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(slab + px * SH::SLAB_ROW + run * 8 + 4);
-                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    lo[j] = *reinterpret_cast<const f32x4 *>(slab + px * SH::SLAB_ROW + run * 8);
+                    hi[j] = *reinterpret_cast<const f32x4 *>(slab + px * SH::SLAB_ROW + run * 8 + 4);
+                }
+                if (t + 1 < 4) put(t + 1);
+#pragma unroll
+                for (int j = 0; j < 2; j++) {
+                    float v[8] = {lo[j][0], lo[j][1], lo[j][2], lo[j][3], hi[j][0], hi[j][1], hi[j][2], hi[j][3]};
                     if (has_res) {
                         const u32x4 r4 = res[t & 1][j];
 #pragma unroll

@@ -257,6 +257,11 @@ void conv3x3_stream_kernel(ConvParams p, int tiles_n, int slots_n)
     // Output: raw buffer stores whose range check does the pixel tail (a pixel past the last lies past the buffer's
     // end); rows past the last output channel get an out-of-range offset.
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.P * (unsigned)p.Cout * 2u), kRsrcFlags);
+    // The eight 32 x 32 pieces of the tile cross the wave's slab one after the other.  A wave's LDS operations execute
+    // in order, so piece t + 1 may be written as soon as the reads of piece t have been *issued*: the conversion and
+    // the writes of the next piece sit between a piece's reads and the stores that wait for them, and cover the slab's
+    // read latency (the largest part of a piece's time otherwise).  (Keeping two pieces' runs in flight would cover
+    // all of it, but the sixteen registers are not there: the weight and activation rings of the next tile are live.)
     auto write_tile = [&](int n0, auto actf) {
         unsigned yoff[TM][2];                         // byte offset of this lane's 16-byte run for pixel subtile 0
 #pragma unroll
@@ -266,28 +271,39 @@ void conv3x3_stream_kernel(ConvParams p, int tiles_n, int slots_n)
                 const int px = (lane >> 2) + 16 * j, o = m0 + (wave * TM + tm) * 32 + (lane & 3) * 8;
                 yoff[tm][j] = o < p.Cout ? (unsigned)((n0 + px) * p.Cout + o) * 2u : kOutOfRange;
             }
+        auto put = [&](int t) {                       // piece t = tm * TN + tn into the slab
+            const int tm = t / TN, tn = t % TN;
 #pragma unroll
-        for (int tm = 0; tm < TM; tm++)
+            for (int q = 0; q < 4; q++) {
+                float r[4];
 #pragma unroll
-            for (int tn = 0; tn < TN; tn++) {
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    float r[4];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) r[e] = actf(acc[tm][tn][4 * q + e]);
-                    *reinterpret_cast<uint2 *>(slab + (lane & 31) * SH::SLAB_ROW + 8 * q + 4 * (lane >> 5)) =
-                        make_uint2(cvt_pack2<ODT>(r[0], r[1]), cvt_pack2<ODT>(r[2], r[3]));
-                }
-                // (a wave's LDS operations execute in order: the reads below see the writes above)
-#pragma unroll
-                for (int j = 0; j < 2; j++) {
-                    const int px = (lane >> 2) + 16 * j, run = lane & 3;
-                    const uint2 lo = *reinterpret_cast<const uint2 *>(slab + px * SH::SLAB_ROW + run * 8);
-                    const uint2 hi = *reinterpret_cast<const uint2 *>(slab + px * SH::SLAB_ROW + run * 8 + 4);
-                    const u32x4 w = {lo.x, lo.y, hi.x, hi.y};
-                    __builtin_amdgcn_raw_buffer_store_b128(w, ry, (int)yoff[tm][j], tn * 32 * p.Cout * 2, 0);
-                }
+                for (int e = 0; e < 4; e++) r[e] = actf(acc[tm][tn][4 * q + e]);
+                *reinterpret_cast<uint2 *>(slab + (lane & 31) * SH::SLAB_ROW + 8 * q + 4 * (lane >> 5)) =
+                    make_uint2(cvt_pack2<ODT>(r[0], r[1]), cvt_pack2<ODT>(r[2], r[3]));
             }
+        };
+        auto get = [&](u32x4 (&w)[2]) {               // this lane's two 16-byte runs of the piece in the slab
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                const int px = (lane >> 2) + 16 * j, run = lane & 3;
+                const uint2 lo = *reinterpret_cast<const uint2 *>(slab + px * SH::SLAB_ROW + run * 8);
+                const uint2 hi = *reinterpret_cast<const uint2 *>(slab + px * SH::SLAB_ROW + run * 8 + 4);
+                w[j] = u32x4{lo.x, lo.y, hi.x, hi.y};
+            }
+        };
+        auto send = [&](int t, const u32x4 (&w)[2]) {
+            const int tm = t / TN, tn = t % TN;
+#pragma unroll
+            for (int j = 0; j < 2; j++) __builtin_amdgcn_raw_buffer_store_b128(w[j], ry, (int)yoff[tm][j], tn * 32 * p.Cout * 2, 0);
+        };
+        put(0);
+#pragma unroll
+        for (int t = 0; t < TM * TN; t++) {
+            u32x4 w[2];
+            get(w);
+            if (t + 1 < TM * TN) put(t + 1);
+            send(t, w);
+        }
     };
 
     // prologue: the first weight fragments, the tile's bias values (parked in LDS by these waves; barrier 0 makes them

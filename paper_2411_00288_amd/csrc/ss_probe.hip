@@ -56,7 +56,8 @@ __global__ __launch_bounds__(512) void issue_probe_kernel(float *sink, int iters
 
 // LDS bandwidth of a compute unit: every wave issues eight independent 16-byte-per-lane LDS instructions, waits for
 // them, and repeats.  MODE 0: reads in the convolution kernels' fragment pattern (lane % 32 = pixel row of `row_bytes`,
-// lane / 32 = second half of the step); MODE 1: lane-linear writes (a wave's 1 KiB contiguous).
+// lane / 32 = second half of the step); MODE 1: lane-linear writes (a wave's 1 KiB contiguous); MODE 2 / 3: the same
+// bytes as 8-byte / 4-byte writes.
 typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
 template <int MODE>
 __global__ __launch_bounds__(1024) void lds_probe_kernel(uint32_t *sink, int iters, int row_bytes)
@@ -79,10 +80,23 @@ __global__ __launch_bounds__(1024) void lds_probe_kernel(uint32_t *sink, int ite
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int j = 0; j < 8; j++) acc ^= v[j][0];
-        } else {
+        } else if constexpr (MODE == 1) {
             const pu32x4 d = {acc, (uint32_t)it, 1u, 2u};
 #pragma unroll
             for (int j = 0; j < 8; j++) asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(wr), "v"(d), "n"((j % 3) * 16384) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        } else if constexpr (MODE == 2) {            // the same bytes as 8-byte writes (a wave's 512 bytes contiguous per instruction)
+            typedef uint32_t pu32x2 __attribute__((ext_vector_type(2)));
+            const pu32x2 d = {acc, (uint32_t)it};
+            const uint32_t wr8 = base + lane * 8 + (w & 15) * 1024;
+#pragma unroll
+            for (int j = 0; j < 16; j++) asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(wr8), "v"(d), "n"((j % 3) * 16384 + (j & 1) * 512) : "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        } else {                                     // ... and as 4-byte writes (256 bytes contiguous per instruction)
+            const uint32_t d = acc + (uint32_t)it;
+            const uint32_t wr4 = base + lane * 4 + (w & 15) * 1024;
+#pragma unroll
+            for (int j = 0; j < 32; j++) asm volatile("ds_write_b32 %0, %1 offset:%2" ::"v"(wr4), "v"(d), "n"((j % 3) * 16384 + (j & 3) * 256) : "memory");
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
     }
@@ -145,7 +159,7 @@ extern "C" int ss_debug_lds_bandwidth(int32_t write, int32_t waves_per_simd, int
     if (scratch_bytes < (size_t)ncu * 1024 * 4) return SS_ERR_WORKSPACE;
     const int threads = 256 * waves_per_simd, iters = 2000;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    auto kern = write ? lds_probe_kernel<1> : lds_probe_kernel<0>;
+    auto kern = write == 0 ? lds_probe_kernel<0> : (write == 1 ? lds_probe_kernel<1> : (write == 2 ? lds_probe_kernel<2> : lds_probe_kernel<3>));
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 65536) != hipSuccess) return SS_ERR_HIP;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SS_ERR_HIP;
