@@ -452,11 +452,12 @@ def print_probes(torch, ss):
     print("## LDS bandwidth of one compute unit, 16 bytes per lane and instruction, eight instructions in flight per wave; "
           "B/clk at the nominal 2.4 GHz")
     for write, what, rows in ((0, "fragment reads", (592, 576, 272, 144)), (1, "lane-linear writes", (16,)),
-                              (2, "... as 8-byte writes", (16,)), (3, "... as 4-byte writes", (16,))):
+                              (2, "... as 8-byte writes", (16,)), (3, "... as 4-byte writes", (16,)),
+                              (4, "half reading, half writing", (592,))):
         for rb in rows:
-            vals = [ss.ss_debug_lds_bandwidth(write, w, rb) for w in (1, 2, 4)]
+            vals = [ss.ss_debug_lds_bandwidth(write, w, rb) for w in ((2, 4) if write == 4 else (1, 2, 4))]
             row = f"{what:20s}" + (f" rows of {rb:3d} B" if not write else "              ")
-            print(row + "  " + "  ".join(f"{w} wave(s)/SIMD: {v:6.1f} GB/s = {v / 2.4:5.1f} B/clk" for w, v in zip((1, 2, 4), vals)), flush=True)
+            print(row + "  " + "  ".join(f"{w} wave(s)/SIMD: {v:6.1f} GB/s = {v / 2.4:5.1f} B/clk" for w, v in zip(((2, 4) if write == 4 else (1, 2, 4)), vals)), flush=True)
 
 
 def main():
@@ -474,7 +475,7 @@ def main():
     ap.add_argument("--profile-run", action="store_true",
                     help="for rocprofv3: one 512 MiB streaming copy (calibrates the traffic counters), then 20 sparse and "
                          "20 dense-twin launches of the benchmark layer, eagerly; prints nothing but a done line")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n500", "cfg1_n512", "cfg2", "s1_c3", "stem"],
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg1_n500", "cfg1_n512", "cfg2", "s1_c3", "s3_c3", "stem"],
                     help="with --profile-run: which layer to launch")
     ap.add_argument("--probes", action="store_true", help="calibration probes (matrix-instruction issue rate, LDS bandwidth) instead of the JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -517,6 +518,7 @@ def main():
         L = {"cfg1": wl.CONFIG1, "cfg1_n500": wl.with_batch(wl.CONFIG1, 500), "cfg1_n512": wl.with_batch(wl.CONFIG1, 512),
              "cfg2": wl.CONFIG2,
              "s1_c3": [l for l in wl.resnet50_layers() if l.name == "s1_c3_1x1_64_256"][0],
+             "s3_c3": [l for l in wl.resnet50_layers() if l.name == "s3_c3_1x1_256_1024"][0],
              "stem": wl.resnet50_layers()[0]}[args.workload]
     run = LayerRun(L, torch, ss, wl, values=not args.profile_run)
 

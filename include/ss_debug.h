@@ -51,7 +51,8 @@ int ss_debug_issue_peak(int32_t dtype, int32_t sparse, void *scratch, size_t scr
  * with one workgroup per compute unit and `waves_per_simd` (1, 2 or 4) waves per SIMD, each issuing eight independent
  * 16-byte-per-lane instructions between waits.  write == 0: reads in the convolution kernels' fragment pattern over
  * pixel rows of `row_bytes` (a multiple of 16, at most 592); write == 1: lane-linear 16-byte writes; write == 2 / 3:
- * the same bytes as 8-byte / 4-byte writes.  `scratch` as for
+ * the same bytes as 8-byte / 4-byte writes; write == 4: even waves read, odd waves write 16 bytes per lane (the sum of
+ * both is reported).  `scratch` as for
  * ss_debug_issue_peak, 4096 bytes per compute unit.  Waits for the stream.
  */
 int ss_debug_lds_bandwidth(int32_t write, int32_t waves_per_simd, int32_t row_bytes, void *scratch, size_t scratch_bytes,

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(512) void issue_probe_kernel(float *sink, int iters
 // LDS bandwidth of a compute unit: every wave issues eight independent 16-byte-per-lane LDS instructions, waits for
 // them, and repeats.  MODE 0: reads in the convolution kernels' fragment pattern (lane % 32 = pixel row of `row_bytes`,
 // lane / 32 = second half of the step); MODE 1: lane-linear writes (a wave's 1 KiB contiguous); MODE 2 / 3: the same
-// bytes as 8-byte / 4-byte writes.
+// bytes as 8-byte / 4-byte writes; MODE 4: even waves read, odd waves write.
 typedef uint32_t pu32x4 __attribute__((ext_vector_type(4)));
 template <int MODE>
 __global__ __launch_bounds__(1024) void lds_probe_kernel(uint32_t *sink, int iters, int row_bytes)
@@ -80,6 +80,21 @@ __global__ __launch_bounds__(1024) void lds_probe_kernel(uint32_t *sink, int ite
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int j = 0; j < 8; j++) acc ^= v[j][0];
+        } else if constexpr (MODE == 4) {            // even waves read, odd waves write (16 bytes per lane each): do the two share the LDS's time?
+            if ((w & 1) == 0) {
+                pu32x4 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v[j]) : "v"(rd), "n"(j * 64));
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int j = 0; j < 8; j++) acc ^= v[j][0];
+            } else {
+                const pu32x4 d = {acc, (uint32_t)it, 1u, 2u};
+                const uint32_t wr2 = wr + 40960;     // (above the rows the readers use)
+#pragma unroll
+                for (int j = 0; j < 8; j++) asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(wr2), "v"(d), "n"((j & 1) * 8192) : "memory");
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
         } else if constexpr (MODE == 1) {
             const pu32x4 d = {acc, (uint32_t)it, 1u, 2u};
 #pragma unroll
@@ -159,7 +174,7 @@ extern "C" int ss_debug_lds_bandwidth(int32_t write, int32_t waves_per_simd, int
     if (scratch_bytes < (size_t)ncu * 1024 * 4) return SS_ERR_WORKSPACE;
     const int threads = 256 * waves_per_simd, iters = 2000;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    auto kern = write == 0 ? lds_probe_kernel<0> : (write == 1 ? lds_probe_kernel<1> : (write == 2 ? lds_probe_kernel<2> : lds_probe_kernel<3>));
+    auto kern = write == 0 ? lds_probe_kernel<0> : (write == 1 ? lds_probe_kernel<1> : (write == 2 ? lds_probe_kernel<2> : (write == 3 ? lds_probe_kernel<3> : lds_probe_kernel<4>)));
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 65536) != hipSuccess) return SS_ERR_HIP;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SS_ERR_HIP;
