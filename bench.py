@@ -38,7 +38,7 @@ SPARSE_INT8_PEAK_TOPS = 10000.0     # 2 x the published dense int8 peak (5.0 POP
 HBM_PEAK_GBS = 8000.0
 # Memory-side bytes per launch of the sparse kernel on configs[1], from the rocprofv3 counter runs summarised in
 # profiles/conv_kernel_hbm_traffic.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (factors from a streaming copy).
-CFG1_TRAFFIC_BYTES = int((2.0 * 4325.1 + 1.0 * 3136.0) * 1024)
+CFG1_TRAFFIC_BYTES = int((2.0 * 4336.1 + 1.0 * 3136.0) * 1024)
 
 
 def _to_dev(bits, dtype, torch, ss):
