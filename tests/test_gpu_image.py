@@ -77,3 +77,33 @@ def test_a_non_finite_pixel_reaches_exactly_the_windows_that_contain_it(ss):
     assert not (bad & ~hit).any(), np.argwhere(bad & ~hit)
     assert (np.isfinite(y[0]).any(axis=-1) | hit).all()
     assert (~np.isfinite(y[0])).any(axis=-1)[hit].all()
+
+
+def test_image_kernel_in_hip_graph_replays_correctly(ss):
+    """Recorded twice in a HIP graph and replayed on changing images with eager work in between: every replay equals
+    the eager result bit for bit."""
+    L = _L(2, 70, 66, 4, 64, korder=wl.K_RSC, dtype=wl.BF16, seed=33)
+    d = wl.make_inputs(L)
+    desc = layer_desc(ss, L)
+    x = dev_bits(d["x"], L.dtype)
+    wbuf = ss.ss_dense_pack(desc, dev_bits(d["W"], L.dtype), None)
+    bias = torch.from_numpy(d["bias"]).cuda()
+    launch, y = ss.prepare_conv2d(desc, x, wbuf, bias, (2, 2), (3, 3), L.act, sparse=False)
+    launch()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            launch()
+            launch()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x.copy_(torch.roll(x, shifts=rep + 1, dims=2))          # new contents, same buffer
+        eager = ss.ss_conv2d_dense_fwd(desc, x, wbuf, bias, (2, 2), (3, 3), L.act)
+        torch.cuda.synchronize()
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
