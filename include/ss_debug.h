@@ -15,8 +15,11 @@ extern "C" {
 
 /*
  * Forces the workgroup tile of the convolution entry points (ss_conv2d_*_fwd) to the kernel variant with this id
- * for all later calls of the process; a negative id returns the choice to the library.  Ids the problem's staging
- * mode has no kernel for fall back to the library's choice.  Process-wide, read with a relaxed atomic load at every
+ * for all later calls of the process; a negative id returns the choice to the library.  Ids: 0-5 the one-tile-per-
+ * workgroup shapes (64x64 shallow / deep, 128x64 shallow, 256x64 deep, 128x64 and 256x64 with producer waves);
+ * 10 / 11 the resident-grid 3x3 kernel with 256x128 / 256x64 tiles; 12 the dense 7x7 first-layer kernel; 13 the
+ * activation-stationary 1x1 kernel.  Ids the problem has no kernel for fall back to the library's choice; with an
+ * id of 10 or more no split of the reduction is planned.  Process-wide, read with a relaxed atomic load at every
  * launch; meant for single-threaded tests.  Always returns SS_OK.  [host]
  */
 int ss_debug_force_tile(int32_t id);
@@ -24,7 +27,9 @@ int ss_debug_force_tile(int32_t id);
 /*
  * Forces the number of workgroups that share one output tile of the 16-bit convolutions, each taking a share of the
  * reduction (see ss_conv2d_workspace_bytes); the value is clamped to the number of reduction chunks, and layers whose
- * staging mode does not split ignore it.  0 or a negative value returns the decision to the library.  The workspace
+ * staging mode does not split ignore it.  (With the activation-stationary 1x1 kernel forced, the value is instead the
+ * number of workgroups that share a pixel tile, each taking a share of the output channels; no workspace is involved.)
+ * 0 or a negative value returns the decision to the library.  The workspace
  * query answers for the forced value, so query after forcing.  Process-wide, as above.  Always returns SS_OK.  [host]
  */
 int ss_debug_force_split(int32_t n);
