@@ -196,6 +196,8 @@ void conv3x3_stream_kernel(ConvParams p, int tiles_n, int slots_n)
     }
 
     // ------------------------------------------------------------------ multiplying waves
+    // (they set the pace -- the producers wait for them at every chunk's barrier -- so they get the issue slots first)
+    __builtin_amdgcn_s_setprio(3);
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.a_vals), 0, (int)p.a_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.a_meta), 0, (int)p.meta_bytes, kRsrcFlags);
     // A weight tile is lane-linear: the lane's share sits at lane * 16 (values) / lane * 4 (index words) from the tile's
