@@ -36,7 +36,10 @@ int SS_CAT(conv_dispatch_, SS_INST_NAME)(const ss_weight_desc *desc, const ConvP
         // ones, whose few output channels leave nothing to walk over.
         // With a residual tail the gain is smaller (the residual runs are fetched by the same waves that multiply), and
         // at 512 channels, where LDS leaves room for one workgroup per compute unit, it turns into a loss.
-        const bool pays = p.Cout >= 2 * desc->cin && p.Cout >= 256 && !(desc->cin >= 512 && p.residual != nullptr);
+        // With few pixel tiles (small batches of the late stages) the long reductions do better in the tiled kernels
+        // (7x7 images, 512 -> 2048: 4.4 vs 5.7 us at batch 1, 4.7 vs 6.0 us at batch 8).
+        const bool pays = p.Cout >= 2 * desc->cin && p.Cout >= 256 && !(desc->cin >= 512 && p.residual != nullptr) &&
+                          (desc->cin <= 128 || (long long)p.P >= 48 * 64);
         if ((forced == 13 || (forced < 0 && pays)) && rows_eligible(desc, p)) {
             int ncu = compute_units();
             if (ncu <= 0) return SS_ERR_HIP;
